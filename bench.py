@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X sparse-lexical LM head: one step = forward + backward of the whole
+hot path over one synthetic batch, inputs resident in HBM.  Prints ONE JSON line.
+
+value      = (valid-token forward flops + backward flops) / time, in TFLOP/s:
+             2 * sum_b(len_b) * D * V  +  4 * nnz * D,  nnz = (b,v) pairs with a non-zero gate.
+             Padded tokens are never counted.
+roofline   = the fused forward kernel (dense contraction, bf16 MFMA) against the 2.5 PFLOP/s peak.
+cpu_baseline = the fp64 NumPy oracle, as it stands, on a bounded vocabulary sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def flops_forward(inp):
+    w = inp.workload
+    return 2.0 * inp.sum_len * w.D * w.V
+
+
+def time_workload(name, steps, warmup, torch, wl, DeviceHead, profile=True):
+    w = wl.WORKLOADS[name]
+    inp = wl.make_inputs(w)
+    torch.cuda.reset_peak_memory_stats()
+    head = DeviceHead(inp)
+    do_bwd = head.has_backward
+
+    def step():
+        head.forward()
+        if do_bwd:
+            head.backward()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for k in range(steps):
+        ev[k][0].record()
+        head.forward()
+        ev[k][1].record()
+        if do_bwd:
+            head.backward()
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    peak_bytes = torch.cuda.max_memory_allocated()
+    ms_step = (t1 - t0) * 1e3 / steps
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps if do_bwd else 0.0
+
+    nnz = 0
+    if do_bwd:
+        nnz = int(((head.Y > 0) & (head.dY != 0)).sum().item())
+    f_fwd = flops_forward(inp)
+    f_bwd = 4.0 * nnz * w.D if do_bwd else 0.0
+    res = {
+        "workload": name, "B": w.B, "S": w.S, "D": w.D, "V": w.V, "sum_len": inp.sum_len, "nnz": nnz,
+        "ms_per_step": ms_step, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "tflops_step": (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12,
+        "fwd_tflops_valid": f_fwd / (fwd_ms * 1e-3) / 1e12,
+        "fwd_tflops_dense": 2.0 * w.B * w.S * w.D * w.V / (fwd_ms * 1e-3) / 1e12,
+        "fwd_frac_mfma_peak": f_fwd / (fwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "peak_hbm_bytes": int(peak_bytes),
+        "logits_avoided_bytes_bf16": int(2 * w.B * w.S * w.V),
+    }
+    if do_bwd:
+        esz = 2
+        comp = (3 * w.B * w.V * 4 + w.B * w.S * w.D * esz + w.V * w.D * esz + w.V * w.D * 4 + w.B * w.S * w.D * 4 + w.V * 4)
+        res["bwd_compulsory_bytes"] = int(comp)
+        res["bwd_gbs_compulsory"] = comp / (bwd_ms * 1e-3) / 1e9
+    if profile:
+        kf = [0.0] * 8
+        kb = [0.0] * 8
+        n = 3
+        for _ in range(n):
+            for i, x in enumerate(head.forward_profiled()):
+                kf[i] += x / n
+            if do_bwd:
+                for i, x in enumerate(head.backward_profiled()):
+                    kb[i] += x / n
+        res["kernel_ms"] = {"fwd_compact": kf[0], "fwd_fused": kf[1], "bwd_count": kb[0], "bwd_scan": kb[1],
+                            "bwd_place": kb[2], "bwd_dH": kb[3], "bwd_dW_db": kb[4]}
+    return res, inp, head
+
+
+def cpu_baseline(inp, n_rows, np):
+    """The oracle on a vocabulary sample of the same batch (first, last and evenly spaced tiles)."""
+    from oracle import lsr_head_oracle as orc
+    w = inp.workload
+    tile = 256
+    n_tiles_all = (w.V + tile - 1) // tile
+    n_tiles = max(2, min(n_tiles_all, n_rows // tile))
+    tiles = np.unique(np.linspace(0, n_tiles_all - 1, n_tiles).round().astype(int))
+    vs = np.concatenate([np.arange(t * tile, min(w.V, (t + 1) * tile)) for t in tiles])
+    Wv, bv = inp.W[vs], inp.bias[vs]
+    dYv = inp.dY[:, vs] if inp.dY is not None else None
+    t0 = time.perf_counter()
+    if dYv is not None:
+        dH, dW, db, g, _ = orc.backward(inp.H, Wv, bv, inp.mask, dYv)     # forward + gate + routing
+        nnz = int((g != 0).sum())
+    else:
+        orc.forward(inp.H, Wv, bv, inp.mask)
+        nnz = 0
+    dt = time.perf_counter() - t0
+    fl = 2.0 * inp.sum_len * w.D * vs.size + 4.0 * nnz * w.D
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "seconds": dt,
+            "sample": f"{vs.size} of {w.V} vocabulary rows ({tiles.size} tiles of 256 incl. first and last), "
+                      f"all {w.B} sequences, forward+backward in fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5_large_fwdbwd")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--cpu-rows", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
+
+    import numpy as np
+    import torch
+    from paper_2603_25011_amd import inputs as wl
+    from paper_2603_25011_amd.harness import DeviceHead
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+
+    res, inp, head = time_workload(args.workload, args.steps, args.warmup, torch, wl, DeviceHead)
+    w = inp.workload
+    fwd_flops = flops_forward(inp)
+    roof = {"bound": "mfma", "kernel": "fwd_bf16_kernel (fused GEMM + max/argmax + activation)",
+            "achieved": fwd_flops / (res["fwd_ms"] * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "traffic": None, "flops_per_launch": fwd_flops, "avg_launch_ms": res["fwd_ms"],
+            "dense_tflops": res["fwd_tflops_dense"]}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    del head
+    torch.cuda.empty_cache()
+
+    extra = {}
+    if not args.no_extra:
+        for name in ("c2_doc_fwd", "c3_query_fwdbwd", "c4_xlmr_fwdbwd"):
+            if name == args.workload:
+                continue
+            r, _, h = time_workload(name, max(5, args.steps), args.warmup, torch, wl, DeviceHead)
+            extra[name] = r
+            del h
+            torch.cuda.empty_cache()
+
+    cpu = None if args.no_cpu else cpu_baseline(inp, args.cpu_rows, np)
+
+    out = {
+        "metric": "fused LM-head fwd+bwd TFLOP/s (valid-token flops) and % MFMA peak; peak HBM bytes",
+        "value": res["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={w.B} S={w.S} D={w.D} V={w.V}, valid lengths {w.len_lo}..{w.len_hi}, "
+                               f"forward+backward" if w.backward else f"{args.workload}: forward only",
+                   "sum_len": inp.sum_len, "nnz": res["nnz"]},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "detail": res,
+        "other_workloads": extra,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

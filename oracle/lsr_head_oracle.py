@@ -114,10 +114,11 @@ def backward_from_gate(H, W, g, I, v_chunk: int = 8192):
     dW = np.zeros((V, D), F64)
     dH = np.zeros((B, S, D), F64)
     for b in range(B):
-        for v0 in range(0, V, v_chunk):
-            v1 = min(V, v0 + v_chunk)
-            dW[v0:v1] += g64[b, v0:v1, None] * H64[b][I[b, v0:v1]]
-        for s in np.unique(I[b][g64[b] != 0.0]):
+        nz = np.flatnonzero(g64[b])                 # pairs with g = 0 contribute nothing
+        for c0 in range(0, nz.size, v_chunk):
+            vs = nz[c0:c0 + v_chunk]                # distinct rows, so the indexed += is exact
+            dW[vs] += g64[b, vs, None] * H64[b][I[b, vs]]
+        for s in np.unique(I[b][nz]):
             sel = I[b] == s
             dH[b, s] = g64[b, sel] @ W64[sel]
     return dH, dW, db

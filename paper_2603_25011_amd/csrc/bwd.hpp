@@ -1,0 +1,320 @@
+// Backward of the sparse-lexical head (paper Sec. 3 "Backward Pass", Alg. 3).
+//
+// Per (b,v) the gradient is g = dY * exp(-Y) where Y > 0 (derivative of log(1+ReLU(x)) written
+// with the saved output), routed to one hidden state H[b, I[b,v]] and one embedding row W[v]:
+//     dW[v,:]   = sum_b g[b,v] * H[b, I[b,v], :]
+//     dH[b,s,:] = sum_{v : I[b,v] = s} g[b,v] * W[v,:]
+//     db[v]     = sum_b g[b,v]
+// The paper accumulates with atomics across blocks.  Here every output row has one owner that
+// gathers its contributions in a fixed order (no global atomics, reproducible sums):
+//   dW/db : the owner of row v walks b = 0..B-1 and gathers rows of H.
+//   dH    : the (b,v) pairs with g != 0 are first bucketed by position s with a stable counting
+//           sort (count -> scan -> place); the owner of row (b,s) then walks its bucket in
+//           ascending v and gathers rows of W.  Empty buckets write zeros, so dH needs no memset.
+// Rows are read as 16-byte chunks: one thread owns chunk c (+128, +256, ...) of the row and keeps
+// fp32 accumulators for it.  All of this is bandwidth-bound row gathering; the arithmetic is plain
+// fp32 FMA.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lsr {
+
+constexpr int ROW_THREADS = 128;     // threads that share one row (16 bytes each per pass)
+
+__device__ __forceinline__ float gate_grad(float dy, float y) { return y > 0.f ? dy * expf(-y) : 0.f; }
+__device__ __forceinline__ int clamp_pos(int s, int S) { return s < 0 ? 0 : (s >= S ? S - 1 : s); }
+
+template <typename T> struct RowChunk;
+template <> struct RowChunk<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void fma(const uint4& x, float g, float* acc) {
+        acc[0] = fmaf(g, __uint_as_float(x.x), acc[0]);
+        acc[1] = fmaf(g, __uint_as_float(x.y), acc[1]);
+        acc[2] = fmaf(g, __uint_as_float(x.z), acc[2]);
+        acc[3] = fmaf(g, __uint_as_float(x.w), acc[3]);
+    }
+};
+template <> struct RowChunk<uint16_t> {       // bfloat16 storage
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void fma(const uint4& x, float g, float* acc) {
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] = fmaf(g, __uint_as_float(w[i] << 16), acc[2 * i]);
+            acc[2 * i + 1] = fmaf(g, __uint_as_float(w[i] & 0xffff0000u), acc[2 * i + 1]);
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Stable bucketing of the non-zero (b,v) pairs by position s.
+// The vocabulary is cut into n_seg segments of seg_len entries; (b, segment) is the unit of work.
+// ---------------------------------------------------------------------------------------------
+
+// cnt[b][seg][s] = number of v in the segment with g != 0 and I[b,v] = s.
+__global__ __launch_bounds__(256) void bwd_count_kernel(const float* __restrict__ dY,
+                                                        const float* __restrict__ Y,
+                                                        const int* __restrict__ I,
+                                                        int* __restrict__ cnt,
+                                                        int S, int V, int n_seg, int seg_len) {
+    extern __shared__ int s_hist[];
+    const int seg = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    for (int s = tid; s < S; s += 256) s_hist[s] = 0;
+    __syncthreads();
+    const int vbeg = seg * seg_len;
+    const int vend = min(V, vbeg + seg_len);
+    const size_t row = (size_t)b * V;
+    for (int v = vbeg + tid; v < vend; v += 256) {
+        const float g = gate_grad(dY[row + v], Y[row + v]);
+        if (g != 0.f) atomicAdd(&s_hist[clamp_pos(I[row + v], S)], 1);
+    }
+    __syncthreads();
+    int* out = cnt + ((size_t)b * n_seg + seg) * S;
+    for (int s = tid; s < S; s += 256) out[s] = s_hist[s];
+}
+
+// Per b: cnt[b][seg][s] becomes the number of earlier-segment entries of bucket s, and
+// bstart[b][0..S] the exclusive prefix of the bucket sizes (bstart[b][S] = non-zero pairs of row b).
+__global__ __launch_bounds__(256) void bwd_scan_kernel(int* __restrict__ cnt, int* __restrict__ bstart,
+                                                       int S, int n_seg) {
+    extern __shared__ int s_tot[];          // [S] bucket sizes, then [256] partials
+    int* s_part = s_tot + S;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    for (int s = tid; s < S; s += 256) {
+        int run = 0;
+        for (int seg = 0; seg < n_seg; ++seg) {
+            const size_t idx = ((size_t)b * n_seg + seg) * S + s;
+            const int c = cnt[idx];
+            cnt[idx] = run;
+            run += c;
+        }
+        s_tot[s] = run;
+    }
+    __syncthreads();
+    const int per = (S + 255) / 256;
+    const int lo = min(S, tid * per), hi = min(S, lo + per);
+    int sum = 0;
+    for (int s = lo; s < hi; ++s) sum += s_tot[s];
+    s_part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int t = 0; t < 256; ++t) { const int c = s_part[t]; s_part[t] = run; run += c; }
+        bstart[(size_t)b * (S + 1) + S] = run;
+    }
+    __syncthreads();
+    int run = s_part[tid];
+    int* out = bstart + (size_t)b * (S + 1);
+    for (int s = lo; s < hi; ++s) { out[s] = run; run += s_tot[s]; }
+}
+
+// One wave per (b, segment) walks its entries in ascending v, 64 at a time.  Lanes holding the
+// same position find each other with one ballot per key bit; the rank among them keeps the order
+// of v, so every bucket ends up sorted by v (stable) and the later sums have a fixed order.
+__global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__ dY,
+                                                       const float* __restrict__ Y,
+                                                       const int* __restrict__ I,
+                                                       const int* __restrict__ cnt,
+                                                       const int* __restrict__ bstart,
+                                                       int* __restrict__ perm_v, float* __restrict__ perm_g,
+                                                       int S, int V, int n_seg, int seg_len, int key_bits) {
+    extern __shared__ int s_off[];          // [S] next free slot of each bucket
+    const int seg = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const int* c0 = cnt + ((size_t)b * n_seg + seg) * S;
+    const int* b0 = bstart + (size_t)b * (S + 1);
+    for (int s = lane; s < S; s += 64) s_off[s] = b0[s] + c0[s];
+    __syncthreads();
+    const int vbeg = seg * seg_len;
+    const int vend = min(V, vbeg + seg_len);
+    const size_t row = (size_t)b * V;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    for (int base = vbeg; base < vend; base += 64) {
+        const int v = base + lane;
+        float g = 0.f;
+        int key = 0;
+        if (v < vend) {
+            g = gate_grad(dY[row + v], Y[row + v]);
+            key = clamp_pos(I[row + v], S);
+        }
+        const bool active = g != 0.f;
+        unsigned long long same = __ballot(active);
+        for (int bit = 0; bit < key_bits; ++bit) {
+            const bool one = (key >> bit) & 1;
+            const unsigned long long bm = __ballot(active && one);
+            same &= one ? bm : ~bm;
+        }
+        const int rank = __popcll(same & lt);
+        const int group = __popcll(same);
+        int dest = 0;
+        if (active) {
+            dest = s_off[key] + rank;
+            perm_v[row + dest] = v;
+            perm_g[row + dest] = g;
+        }
+        __syncthreads();
+        if (active && rank == group - 1) s_off[key] = dest + 1;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dH[b,s,:] = sum over the bucket of (b,s), in ascending v, of g * W[v,:].   grid (S, B)
+// ---------------------------------------------------------------------------------------------
+template <typename T, int CPT>
+__global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict__ W,
+                                                             const int* __restrict__ bstart,
+                                                             const int* __restrict__ perm_v,
+                                                             const float* __restrict__ perm_g,
+                                                             float* __restrict__ dH,
+                                                             int S, int D, int V) {
+    constexpr int N = RowChunk<T>::N;
+    __shared__ int s_v[ROW_THREADS];
+    __shared__ float s_g[ROW_THREADS];
+    const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int n_chunks = D / N;
+    const int beg = bstart[(size_t)b * (S + 1) + s];
+    const int end = bstart[(size_t)b * (S + 1) + s + 1];
+    const size_t prow = (size_t)b * V;
+    float acc[CPT][N];
+#pragma unroll
+    for (int cp = 0; cp < CPT; ++cp)
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[cp][i] = 0.f;
+
+    for (int base = beg; base < end; base += ROW_THREADS) {
+        const int n = min(ROW_THREADS, end - base);
+        s_v[tid] = tid < n ? perm_v[prow + base + tid] : 0;     // padding: row 0 with weight 0
+        s_g[tid] = tid < n ? perm_g[prow + base + tid] : 0.f;
+        __syncthreads();
+        for (int k = 0; k < n; k += 4) {
+            uint4 x[4][CPT];
+            float g[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                g[u] = s_g[k + u];
+                const T* src = W + (size_t)s_v[k + u] * D;
+#pragma unroll
+                for (int cp = 0; cp < CPT; ++cp) {
+                    const int c = tid + cp * ROW_THREADS;
+                    x[u][cp] = c < n_chunks ? *reinterpret_cast<const uint4*>(src + c * N) : make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int cp = 0; cp < CPT; ++cp) RowChunk<T>::fma(x[u][cp], g[u], acc[cp]);
+        }
+        __syncthreads();
+    }
+    float* out = dH + ((size_t)b * S + s) * D;
+#pragma unroll
+    for (int cp = 0; cp < CPT; ++cp) {
+        const int c = tid + cp * ROW_THREADS;
+        if (c < n_chunks) {
+#pragma unroll
+            for (int i = 0; i < N; i += 4)
+                *reinterpret_cast<float4*>(out + c * N + i) =
+                    make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dW[v,:] = sum_b g[b,v] * H[b, I[b,v], :],  db[v] = sum_b g[b,v].
+// A workgroup owns VT consecutive vocabulary rows.  It first stages g and I for all B x VT pairs in
+// LDS (coalesced along v), then walks the rows one by one, skipping pairs with g = 0.
+// dynamic LDS: B*VT floats + B*VT ints.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int CPT>
+__global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict__ H,
+                                                             const float* __restrict__ dY,
+                                                             const float* __restrict__ Y,
+                                                             const int* __restrict__ I,
+                                                             float* __restrict__ dW, float* __restrict__ db,
+                                                             int B, int S, int D, int V, int VT) {
+    constexpr int N = RowChunk<T>::N;
+    extern __shared__ int s_dyn[];
+    float* s_g = reinterpret_cast<float*>(s_dyn);          // [B][VT]
+    int* s_i = s_dyn + (size_t)B * VT;                     // [B][VT]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int v0 = blockIdx.x * VT;
+    const int n_chunks = D / N;
+
+    for (int e = tid; e < B * VT; e += ROW_THREADS) {
+        const int bb = e / VT, vv = e - bb * VT;
+        const int v = v0 + vv;
+        float g = 0.f;
+        int idx = 0;
+        if (v < V) {
+            const size_t o = (size_t)bb * V + v;
+            g = gate_grad(dY[o], Y[o]);
+            idx = clamp_pos(I[o], S);
+        }
+        s_g[e] = g;
+        s_i[e] = idx;
+    }
+    __syncthreads();
+
+    for (int vv = 0; vv < VT; ++vv) {
+        const int v = v0 + vv;
+        if (v >= V) break;
+        float acc[CPT][N];
+#pragma unroll
+        for (int cp = 0; cp < CPT; ++cp)
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[cp][i] = 0.f;
+        float gsum = 0.f;
+        for (int bb0 = 0; bb0 < B; bb0 += 64) {
+            const int bl = bb0 + lane;
+            const float gl = bl < B ? s_g[bl * VT + vv] : 0.f;
+            gsum += gl;
+            unsigned long long nz = dW ? __ballot(gl != 0.f) : 0ull;       // same in both waves
+            while (nz) {
+                uint4 x[4][CPT];
+                float g[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // take the next non-zero pair, or repeat a harmless one with weight 0
+                    const int bit = nz ? __builtin_ctzll(nz) : 0;
+                    const bool have = nz != 0;
+                    nz = have ? nz & (nz - 1) : 0;
+                    const int bb = bb0 + bit;
+                    g[u] = have ? s_g[bb * VT + vv] : 0.f;
+                    const int idx = have ? s_i[bb * VT + vv] : 0;
+                    const T* src = H + ((size_t)(have ? bb : 0) * S + idx) * D;
+#pragma unroll
+                    for (int cp = 0; cp < CPT; ++cp) {
+                        const int c = tid + cp * ROW_THREADS;
+                        x[u][cp] = c < n_chunks ? *reinterpret_cast<const uint4*>(src + c * N) : make_uint4(0, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int cp = 0; cp < CPT; ++cp) RowChunk<T>::fma(x[u][cp], g[u], acc[cp]);
+            }
+        }
+        float* out = dW + (size_t)v * D;
+        if (dW) {
+#pragma unroll
+            for (int cp = 0; cp < CPT; ++cp) {
+                const int c = tid + cp * ROW_THREADS;
+                if (c < n_chunks) {
+#pragma unroll
+                    for (int i = 0; i < N; i += 4)
+                        *reinterpret_cast<float4*>(out + c * N + i) =
+                            make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+                }
+            }
+        }
+        if (db && tid < 64) {                                    // fixed-order butterfly over b
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o);
+            if (tid == 0) db[v] = gsum;
+        }
+    }
+}
+
+}  // namespace lsr

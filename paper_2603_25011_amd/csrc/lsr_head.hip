@@ -1,0 +1,332 @@
+// C ABI of the MI355X sparse-lexical LM head: host-side validation, workspace layout and kernel
+// launches.  See include/lsr_head.h for the contract of every entry point.
+#include "lsr_head.h"
+
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include "bwd.hpp"
+#include "fwd_bf16.hpp"
+#include "fwd_misc.hpp"
+
+namespace {
+
+using namespace lsr;
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Shape {
+    int B, S, D, V;
+    int dtype;
+};
+
+int check_desc(const lsr_head_desc* d, Shape* out) {
+    if (!d) return LSR_ERR_NULL;
+    if (d->hw_dtype != LSR_F32 && d->hw_dtype != LSR_BF16) return LSR_ERR_DTYPE;
+    if (d->B < 1 || d->S < 1 || d->D < 1 || d->V < 1) return LSR_ERR_SHAPE;
+    if (d->D % 8 != 0 || d->D > 8192 || d->S > 32768 || d->B > 65535) return LSR_ERR_SHAPE;
+    if (d->B * d->S >= (int64_t(1) << 31) || d->B * d->V >= (int64_t(1) << 31)) return LSR_ERR_SHAPE;
+    if (d->V >= (int64_t(1) << 31) - 4096) return LSR_ERR_SHAPE;
+    out->B = (int)d->B; out->S = (int)d->S; out->D = (int)d->D; out->V = (int)d->V;
+    out->dtype = d->hw_dtype;
+    return LSR_OK;
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// ---- forward workspace: len[B] | pos[B*S] ----
+struct FwdWs { size_t len_off, pos_off, total; };
+FwdWs fwd_ws(const Shape& s) {
+    FwdWs w;
+    w.len_off = 0;
+    w.pos_off = align_up(sizeof(int) * (size_t)s.B);
+    w.total = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
+    return w;
+}
+
+// ---- backward workspace: perm_v[B*V] | perm_g[B*V] | cnt[B*n_seg*S] | bstart[B*(S+1)] ----
+struct BwdWs { int n_seg, seg_len, key_bits; size_t pv_off, pg_off, cnt_off, bs_off, total; };
+BwdWs bwd_ws(const Shape& s) {
+    BwdWs w;
+    // enough (b, segment) waves to fill the chip, segments of at least 512 entries, and a count
+    // table no larger than B*V ints
+    long n = 4096 / s.B;
+    n = n < s.V / 512 ? n : s.V / 512;
+    n = n < s.V / s.S ? n : s.V / s.S;
+    if (n < 1) n = 1;
+    w.n_seg = (int)n;
+    w.seg_len = ((s.V + w.n_seg - 1) / w.n_seg + 63) / 64 * 64;
+    w.n_seg = (s.V + w.seg_len - 1) / w.seg_len;
+    w.key_bits = 0;
+    while ((1 << w.key_bits) < s.S) ++w.key_bits;
+    const size_t bv = (size_t)s.B * s.V;
+    w.pv_off = 0;
+    w.pg_off = w.pv_off + align_up(sizeof(int) * bv);
+    w.cnt_off = w.pg_off + align_up(sizeof(float) * bv);
+    w.bs_off = w.cnt_off + align_up(sizeof(int) * (size_t)s.B * w.n_seg * s.S);
+    w.total = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
+    return w;
+}
+
+int check_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
+    static int ok_dev[64] = {0};
+    if (dev >= 0 && dev < 64 && ok_dev[dev]) return LSR_OK;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return LSR_ERR_ARCH;
+    if (dev >= 0 && dev < 64) ok_dev[dev] = 1;
+    return LSR_OK;
+}
+
+// Optional per-kernel event timing (the *_profiled entry points).
+struct Prof {
+    bool on = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[LSR_PROFILE_SLOTS][2];
+    bool used[LSR_PROFILE_SLOTS] = {false};
+    bool fail = false;
+    void begin(int slot) {
+        if (!on) return;
+        if (hipEventCreate(&ev[slot][0]) != hipSuccess || hipEventCreate(&ev[slot][1]) != hipSuccess) { fail = true; return; }
+        used[slot] = true;
+        if (hipEventRecord(ev[slot][0], stream) != hipSuccess) fail = true;
+    }
+    void end(int slot) {
+        if (!on || !used[slot]) return;
+        if (hipEventRecord(ev[slot][1], stream) != hipSuccess) fail = true;
+    }
+    int finish(float* ms) {
+        if (!on) return LSR_OK;
+        if (hipStreamSynchronize(stream) != hipSuccess) fail = true;
+        for (int i = 0; i < LSR_PROFILE_SLOTS; ++i) {
+            ms[i] = 0.f;
+            if (used[i]) {
+                if (!fail && hipEventElapsedTime(&ms[i], ev[i][0], ev[i][1]) != hipSuccess) fail = true;
+                (void)hipEventDestroy(ev[i][0]);
+                (void)hipEventDestroy(ev[i][1]);
+            }
+        }
+        return fail ? LSR_ERR_LAUNCH : LSR_OK;
+    }
+};
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : LSR_ERR_LAUNCH; }
+
+template <bool LONG, int G>
+void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
+    const int grid = (p.n_logical + 7) / 8 * 8;
+    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true>), dim3(grid), dim3(FWD_THREADS), 0, st, p);
+    else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false>), dim3(grid), dim3(FWD_THREADS), 0, st, p);
+}
+
+int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
+                 const uint8_t* mask, float* Y, int32_t* I, void* ws, size_t ws_bytes, void* stream,
+                 Prof& prof) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc != LSR_OK) return rc;
+    if (!H || !W || !bias || !mask || !Y) return LSR_ERR_NULL;
+    if (misaligned(H) || misaligned(W) || misaligned(bias) || misaligned(Y) || (I && misaligned(I)) || misaligned(ws))
+        return LSR_ERR_ALIGN;
+    const FwdWs w = fwd_ws(s);
+    if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
+    rc = check_device();
+    if (rc != LSR_OK) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    prof.stream = st;
+    int* len = reinterpret_cast<int*>(static_cast<char*>(ws) + w.len_off);
+    int* pos = reinterpret_cast<int*>(static_cast<char*>(ws) + w.pos_off);
+
+    prof.begin(0);
+    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
+    prof.end(0);
+    if ((rc = launch_status()) != LSR_OK) return rc;
+
+    prof.begin(1);
+    if (s.dtype == LSR_F32) {
+        dim3 grid((s.V + F32_THREADS - 1) / F32_THREADS, s.B);
+        if (I) hipLaunchKernelGGL((fwd_f32_kernel<true>), grid, dim3(F32_THREADS), 0, st,
+                                  static_cast<const float*>(H), static_cast<const float*>(W), bias, len, pos, Y, I, s.S, s.D, s.V);
+        else   hipLaunchKernelGGL((fwd_f32_kernel<false>), grid, dim3(F32_THREADS), 0, st,
+                                  static_cast<const float*>(H), static_cast<const float*>(W), bias, len, pos, Y, I, s.S, s.D, s.V);
+    } else {
+        FwdParams p;
+        p.H = static_cast<const uint16_t*>(H);
+        p.W = static_cast<const uint16_t*>(W);
+        p.bias = bias; p.len = len; p.pos = pos; p.Y = Y; p.I = I;
+        p.B = s.B; p.S = s.S; p.D = s.D; p.V = s.V;
+        p.n_vtiles = (s.V + FWD_TN - 1) / FWD_TN;
+        const int n_vgroups = (p.n_vtiles + FWD_GV - 1) / FWD_GV;
+        if (s.S > 128) {
+            p.n_rowgroups = s.B;
+            p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
+            launch_fwd_bf16<true, 4>(p, I != nullptr, st);
+        } else {
+            const int G = s.S <= 32 ? 1 : (s.S <= 64 ? 2 : 4);
+            const int spt = FWD_TM / (32 * G);
+            p.n_rowgroups = (s.B + spt - 1) / spt;
+            p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
+            if (G == 1) launch_fwd_bf16<false, 1>(p, I != nullptr, st);
+            else if (G == 2) launch_fwd_bf16<false, 2>(p, I != nullptr, st);
+            else launch_fwd_bf16<false, 4>(p, I != nullptr, st);
+        }
+    }
+    prof.end(1);
+    return launch_status();
+}
+
+template <typename T>
+void launch_dh(int cpt, dim3 grid, hipStream_t st, const T* W, const int* bstart, const int* pv, const float* pg,
+               float* dH, int S, int D, int V) {
+    switch (cpt) {
+        case 1: hipLaunchKernelGGL((bwd_dh_kernel<T, 1>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+        case 2: hipLaunchKernelGGL((bwd_dh_kernel<T, 2>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+        case 4: hipLaunchKernelGGL((bwd_dh_kernel<T, 4>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+        case 8: hipLaunchKernelGGL((bwd_dh_kernel<T, 8>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+        default: hipLaunchKernelGGL((bwd_dh_kernel<T, 16>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+    }
+}
+
+template <typename T>
+void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const float* dY, const float* Y, const int* I,
+               float* dW, float* db, int B, int S, int D, int V, int VT) {
+    switch (cpt) {
+        case 1: hipLaunchKernelGGL((bwd_dw_kernel<T, 1>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+        case 2: hipLaunchKernelGGL((bwd_dw_kernel<T, 2>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+        case 4: hipLaunchKernelGGL((bwd_dw_kernel<T, 4>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+        case 8: hipLaunchKernelGGL((bwd_dw_kernel<T, 8>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+        default: hipLaunchKernelGGL((bwd_dw_kernel<T, 16>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+    }
+}
+
+int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
+                  const int32_t* I, float* dH, float* dW, float* db, void* ws, size_t ws_bytes, void* stream,
+                  Prof& prof) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc != LSR_OK) return rc;
+    if (!H || !W || !dY || !Y || !I) return LSR_ERR_NULL;
+    if (misaligned(H) || misaligned(W) || misaligned(dY) || misaligned(Y) || misaligned(I) || misaligned(ws) ||
+        (dH && misaligned(dH)) || (dW && misaligned(dW)) || (db && misaligned(db)))
+        return LSR_ERR_ALIGN;
+    if (s.S > 8192 || s.B > 6144) return LSR_ERR_SHAPE;      // LDS tables of the bucket sort / dW staging
+    const BwdWs w = bwd_ws(s);
+    if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
+    rc = check_device();
+    if (rc != LSR_OK) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    prof.stream = st;
+    char* base = static_cast<char*>(ws);
+    int* perm_v = reinterpret_cast<int*>(base + w.pv_off);
+    float* perm_g = reinterpret_cast<float*>(base + w.pg_off);
+    int* cnt = reinterpret_cast<int*>(base + w.cnt_off);
+    int* bstart = reinterpret_cast<int*>(base + w.bs_off);
+
+    const int chunk_elems = s.dtype == LSR_F32 ? 4 : 8;
+    const int n_chunks = s.D / chunk_elems;
+    int cpt = 1;
+    while (cpt * ROW_THREADS < n_chunks) cpt *= 2;
+
+    if (dH) {
+        const dim3 seg_grid(w.n_seg, s.B);
+        prof.begin(0);
+        hipLaunchKernelGGL(bwd_count_kernel, seg_grid, dim3(256), sizeof(int) * s.S, st, dY, Y, I, cnt, s.S, s.V, w.n_seg, w.seg_len);
+        prof.end(0);
+        if ((rc = launch_status()) != LSR_OK) return rc;
+        prof.begin(1);
+        hipLaunchKernelGGL(bwd_scan_kernel, dim3(s.B), dim3(256), sizeof(int) * (s.S + 256), st, cnt, bstart, s.S, w.n_seg);
+        prof.end(1);
+        if ((rc = launch_status()) != LSR_OK) return rc;
+        prof.begin(2);
+        hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm_v, perm_g,
+                           s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+        prof.end(2);
+        if ((rc = launch_status()) != LSR_OK) return rc;
+        prof.begin(3);
+        const dim3 grid(s.S, s.B);
+        if (s.dtype == LSR_F32) launch_dh<float>(cpt, grid, st, static_cast<const float*>(W), bstart, perm_v, perm_g, dH, s.S, s.D, s.V);
+        else launch_dh<uint16_t>(cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm_v, perm_g, dH, s.S, s.D, s.V);
+        prof.end(3);
+        if ((rc = launch_status()) != LSR_OK) return rc;
+    }
+    if (dW || db) {
+        // rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
+        int VT = 32;
+        while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
+        if ((size_t)s.B * VT * 8 > 48 * 1024) return LSR_ERR_SHAPE;    // B > 6144
+        const size_t lds = (size_t)s.B * VT * 8;
+        const dim3 grid((s.V + VT - 1) / VT);
+        prof.begin(4);
+        if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+        else launch_dw<uint16_t>(cpt, grid, lds, st, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+        prof.end(4);
+        if ((rc = launch_status()) != LSR_OK) return rc;
+    }
+    return LSR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lsr_head_workspace_bytes(const lsr_head_desc* desc, int for_backward) {
+    Shape s;
+    if (check_desc(desc, &s) != LSR_OK) return 0;
+    return for_backward ? bwd_ws(s).total : fwd_ws(s).total;
+}
+
+int lsr_head_forward(const lsr_head_desc* desc, const void* H, const void* W, const float* bias, const uint8_t* mask,
+                     float* Y, int32_t* I, void* workspace, size_t workspace_bytes, void* stream) {
+    Prof prof;
+    return forward_impl(desc, H, W, bias, mask, Y, I, workspace, workspace_bytes, stream, prof);
+}
+
+int lsr_head_backward(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
+                      const int32_t* I, float* dH, float* dW, float* db, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    Prof prof;
+    return backward_impl(desc, H, W, dY, Y, I, dH, dW, db, workspace, workspace_bytes, stream, prof);
+}
+
+int lsr_head_forward_profiled(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
+                              const uint8_t* mask, float* Y, int32_t* I, void* workspace, size_t workspace_bytes,
+                              void* stream, float* kernel_ms) {
+    if (!kernel_ms) return LSR_ERR_NULL;
+    Prof prof;
+    prof.on = true;
+    const int rc = forward_impl(desc, H, W, bias, mask, Y, I, workspace, workspace_bytes, stream, prof);
+    const int rc2 = prof.finish(kernel_ms);
+    return rc != LSR_OK ? rc : rc2;
+}
+
+int lsr_head_backward_profiled(const lsr_head_desc* desc, const void* H, const void* W, const float* dY,
+                               const float* Y, const int32_t* I, float* dH, float* dW, float* db, void* workspace,
+                               size_t workspace_bytes, void* stream, float* kernel_ms) {
+    if (!kernel_ms) return LSR_ERR_NULL;
+    Prof prof;
+    prof.on = true;
+    const int rc = backward_impl(desc, H, W, dY, Y, I, dH, dW, db, workspace, workspace_bytes, stream, prof);
+    const int rc2 = prof.finish(kernel_ms);
+    return rc != LSR_OK ? rc : rc2;
+}
+
+const char* lsr_status_string(int status) {
+    switch (status) {
+        case LSR_OK: return "ok";
+        case LSR_ERR_NULL: return "a required pointer is NULL";
+        case LSR_ERR_SHAPE: return "shape outside the supported range";
+        case LSR_ERR_DTYPE: return "unknown hw_dtype";
+        case LSR_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case LSR_ERR_WORKSPACE: return "workspace missing or too small";
+        case LSR_ERR_ARCH: return "no gfx950 device";
+        case LSR_ERR_LAUNCH: return "HIP launch or event error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

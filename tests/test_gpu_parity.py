@@ -1,0 +1,142 @@
+"""Parity of the HIP path against the fp64 oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_25011_amd import inputs as wl
+from paper_2603_25011_amd.harness import DeviceHead
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(inp, mask=None, want_index=True, check_bwd=True):
+    head = DeviceHead(inp, mask=mask, want_index=want_index)
+    head.poison_outputs()
+    head.forward()
+    torch.cuda.synchronize()
+    Y = head.Y.cpu().numpy()
+    I = head.I.cpu().numpy() if want_index else None
+    _, _, _, stats = parity.compare_forward(inp, Y, I, mask=mask)
+    m = inp.mask if mask is None else mask
+    empty = ~(m != 0).any(axis=1)
+    assert np.all(Y[empty] == 0.0)
+    assert np.all(Y >= 0.0)
+    if want_index:
+        assert np.all(I[empty] == 0)
+    if check_bwd and head.has_backward and want_index:
+        head.backward()
+        torch.cuda.synchronize()
+        dH, dW, db = head.dH.cpu().numpy(), head.dW.cpu().numpy(), head.db.cpu().numpy()
+        stats.update(parity.compare_backward(inp, I, dH, dW, db, mask=mask))
+        # positions that cannot be selected receive exactly zero
+        assert np.all(dH[m == 0] == 0.0)
+        # same call again: owner-computes sums are bit-reproducible
+        head.backward()
+        torch.cuda.synchronize()
+        assert torch.equal(head.dH.cpu(), torch.from_numpy(dH))
+        assert torch.equal(head.dW.cpu(), torch.from_numpy(dW))
+        assert torch.equal(head.db.cpu(), torch.from_numpy(db))
+    return stats
+
+
+def test_c1_tiny_fp32_forward_backward():
+    print(run_case(wl.make_inputs(wl.WORKLOADS["c1_tiny_f32"])))
+
+
+@pytest.mark.parametrize("B,S,D,V,len_lo", [
+    (20, 32, 128, 700, 1),      # short layout, 1 row block per sequence, partial last tile, ragged V
+    (7, 48, 64, 300, 5),        # short layout, 2 row blocks per sequence
+    (5, 100, 192, 513, 3),      # short layout, 4 row blocks per sequence
+    (3, 300, 256, 1000, 200),   # long layout, two chunks for some rows
+    (2, 129, 200, 260, 1),      # long layout, K tail (D not a multiple of 64)
+    (4, 1, 64, 257, 1),         # S = 1: a plain linear layer
+    (9, 700, 64, 96, 1),        # three chunks, single narrow vocabulary tile
+])
+def test_small_bf16_shapes(B, S, D, V, len_lo):
+    inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
+    print(run_case(inp))
+
+
+def test_fp32_small_shapes():
+    print(run_case(wl.make_custom(3, 20, 72, 333, dtype="f32", seed=5, w_std=0.05)))
+
+
+def test_scattered_mask_and_empty_rows():
+    inp = wl.make_custom(6, 150, 128, 600, seed=77)
+    rng = np.random.default_rng(3)
+    mask = wl.scattered_mask(rng, 6, 150, keep=0.4)
+    mask[2, :] = 0
+    mask[4, :] = 0
+    mask[4, 149] = 1
+    print(run_case(inp, mask=mask))
+    inp2 = wl.make_custom(40, 30, 64, 300, seed=78)
+    mask2 = wl.scattered_mask(rng, 40, 30, keep=0.3)
+    mask2[0, :] = 0
+    mask2[39, :] = 0
+    print(run_case(inp2, mask=mask2))
+
+
+def test_forced_exact_ties_pick_lowest_position():
+    inp = wl.make_custom(2, 40, 64, 500, seed=9, len_lo=40)
+    for arr in (inp.H, inp.H_bits):
+        arr[0, 33] = arr[0, 2]
+        arr[0, 17] = arr[0, 2]
+        arr[1, 39] = arr[1, 0]
+    head = DeviceHead(inp)
+    head.forward()
+    torch.cuda.synchronize()
+    I = head.I.cpu().numpy()
+    assert not np.any((I[0] == 33) | (I[0] == 17)) and not np.any(I[1] == 39)
+    parity.compare_forward(inp, head.Y.cpu().numpy(), I)
+    inp = wl.make_custom(1, 600, 64, 300, seed=10, len_lo=600)
+    for arr in (inp.H, inp.H_bits):
+        arr[0, 599] = arr[0, 100]          # twins in different chunks and different waves
+        arr[0, 300] = arr[0, 100]
+        arr[0, 200] = arr[0, 7]
+    head = DeviceHead(inp)
+    head.forward()
+    torch.cuda.synchronize()
+    I = head.I.cpu().numpy()
+    assert not np.any((I == 599) | (I == 300) | (I == 200))
+    parity.compare_forward(inp, head.Y.cpu().numpy(), I)
+
+
+def test_forward_without_index_output():
+    inp = wl.make_custom(3, 300, 128, 700, seed=12, len_lo=10)
+    print(run_case(inp, want_index=False))
+    inp = wl.make_custom(12, 32, 128, 700, seed=13)
+    print(run_case(inp, want_index=False))
+
+
+def test_backward_output_subsets():
+    inp = wl.make_custom(4, 64, 128, 520, seed=21)
+    head = DeviceHead(inp)
+    head.forward()
+    head.backward()
+    torch.cuda.synchronize()
+    ref = (head.dH.clone(), head.dW.clone(), head.db.clone())
+    from paper_2603_25011_amd import binding as b
+    shape = (head.B, head.S, head.D, head.V, head.dt)
+    for keep in ((1, 0, 0), (0, 1, 0), (0, 0, 1), (0, 1, 1)):
+        head.poison_outputs()
+        head.forward()
+        b.lsr_head_backward(*shape, head.H, head.W, head.dY, head.Y, head.I,
+                            head.dH if keep[0] else None, head.dW if keep[1] else None,
+                            head.db if keep[2] else None, head.ws_bwd)
+        torch.cuda.synchronize()
+        for k, out, r in zip(keep, (head.dH, head.dW, head.db), ref):
+            if k:
+                assert torch.equal(out, r)
+            else:
+                assert torch.isnan(out).all()
+
+
+def test_c2_document_encoding_forward_full():
+    inp = wl.make_inputs(wl.WORKLOADS["c2_doc_fwd"])
+    print(run_case(inp, check_bwd=False))
+
+
+def test_c3_query_encoding_forward_backward_full():
+    inp = wl.make_inputs(wl.WORKLOADS["c3_query_fwdbwd"])
+    print(run_case(inp))
