@@ -133,6 +133,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a 1 GiB device-to-device copy (reference reading for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
@@ -167,6 +169,13 @@ def main():
             torch.cuda.empty_cache()
 
     cpu = None if args.no_cpu else cpu_baseline(inp, args.cpu_rows, np)
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     out = {
         "metric": "fused LM-head fwd+bwd TFLOP/s (valid-token flops) and % MFMA peak; peak HBM bytes",

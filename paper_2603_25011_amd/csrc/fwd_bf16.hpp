@@ -5,16 +5,25 @@
 // taken on raw logits while they still sit in accumulator registers and the activation is
 // applied once afterwards.  The B x S x V logits never leave the chip.
 //
-// Tiling.  A workgroup of 8 waves owns a 256 (tokens) x 256 (vocabulary) output tile; wave
-// (wm, wn) owns rows [128 wm, 128 wm + 128) x columns [64 wn, 64 wn + 64) as 4 x 2 blocks of the
-// 32x32x16 bf16 MFMA.  Tokens are the MFMA's row dimension: in the 32x32 accumulator layout a
-// lane holds 16 rows of ONE column, so the max over tokens starts as a plain in-lane reduction.
-// K (the hidden size D) is walked in slabs of 64 through a double-buffered, XOR-swizzled LDS tile.
+// Tiling.  A workgroup of 8 waves (2 per SIMD) owns a 256 (tokens) x 256 (vocabulary) output tile;
+// wave (wm, wn) owns four 32-row blocks x columns [64 wn, 64 wn + 64), i.e. 4 x 2 blocks of the
+// 32x32x16 bf16 MFMA.  Tokens are the MFMA's row dimension: in the 32x32 accumulator layout a lane
+// holds 16 rows of ONE column, so the max over tokens starts as a plain in-lane reduction, is
+// finished with one exchange between the two half-waves, and (long layout) one exchange through
+// LDS between the two waves that share the columns.
+//
+// Operand staging.  K (the hidden size D) is walked in slabs of BK elements through an NS-stage
+// ring of LDS tiles.  Two loaders:
+//   DMA = true  : global_load_lds (16 bytes per lane straight into LDS, no staging registers),
+//                 slabs issued NS-1 iterations ahead, one barrier per slab.  Needs D % BK == 0.
+//   DMA = false : global -> registers -> LDS, one slab ahead (BK = 64, NS = 2).  Handles any D that
+//                 is a multiple of 8 (the last slab is zero-filled).
+// Rows are XOR-swizzled inside a slab so that the 16-byte fragment reads are bank-conflict free.
 //
 // Masking.  Only valid tokens are multiplied: a compaction pass lists the valid positions of every
 // sequence, and tile rows are gathered through that list.  Rows past the end of a sequence repeat
 // its last valid token, which cannot change a maximum or its lowest-index arg-max, so the
-// epilogue needs no per-element mask.
+// epilogue needs no per-element mask.  Whole 32-row blocks past the end are not multiplied at all.
 //
 // Two row layouts, chosen on the host from S alone:
 //   long  (S > 128): a workgroup owns one sequence and walks its valid tokens in chunks of 256
@@ -25,6 +34,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace lsr {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -32,7 +43,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int FWD_TM = 256;        // tile rows (tokens)
 constexpr int FWD_TN = 256;        // tile columns (vocabulary entries)
-constexpr int FWD_BK = 64;         // K slab (bf16 elements) = 128 bytes per row
 constexpr int FWD_THREADS = 512;
 constexpr int FWD_GV = 4;          // vocabulary tiles per L2-sharing group
 
@@ -50,18 +60,88 @@ struct FwdParams {
     int n_logical;       // ceil(n_vtiles / GV) * GV * n_rowgroups
 };
 
-// Byte offset of 16-byte chunk c (0..7) of row r inside a [256 x 128 B] LDS slab.
-__device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + (((c ^ r) & 7) << 4); }
-
-// Row (0..127 within the wave's 128 rows) of accumulator element e = 16*block + reg for a lane in
-// the given half-wave: MFMA 32x32 output register r of lane l is row 8*(r/4) + 4*(l/32) + r%4.
-__device__ __forceinline__ int acc_row(int e, int half) {
-    return (e >> 4) * 32 + ((e & 15) >> 2) * 8 + half * 4 + (e & 3);
+// Swizzle of the 16-byte chunk index inside a tile row.  A fragment read has lanes 0..31 on 32
+// consecutive rows of one chunk column and lanes 32..63 on the next column; LDS serves 16 lanes
+// (256 bytes, all 64 banks) per cycle.  Measured on gfx950 with 4 waves reading: 128-byte rows
+// XORed with row bits 1..3, or 64-byte rows XORed with row bits 2..3, take 4 cycles per wave
+// read (conflict free); XOR with the low row bits takes 8; no swizzle 32.
+template <int BK>
+__device__ __forceinline__ int lds_swz(int r) {
+    return BK == 64 ? (r >> 1) & 7 : (r >> 2) & 3;
 }
 
-template <bool LONG, int G, bool ARG>
+// Tile row of accumulator element e = 16*i + reg (i = the wave's i-th row block) for a lane in the
+// given half-wave: MFMA 32x32 output register r of lane l is row 8*(r/4) + 4*(l/32) + r%4 of its block.
+template <bool LONG>
+__device__ __forceinline__ int acc_row(int e, int half, int wm) {
+    const int blk = LONG ? 2 * (e >> 4) + wm : 4 * wm + (e >> 4);
+    return blk * 32 + ((e & 15) >> 2) * 8 + half * 4 + (e & 3);
+}
+
+// One K slab of MFMAs for the first NA of this wave's four row blocks.
+template <int NA, int KS>
+__device__ __forceinline__ void mma_slab(const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
+                                         const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 fa[NA], fb[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks]);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks]);
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
+    }
+}
+
+template <int NA, int KS>
+__device__ __forceinline__ void mma_dispatch(int na, const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
+                                             const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
+    switch (na) {
+        case 4: mma_slab<4, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 3: mma_slab<3, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 2: mma_slab<2, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 1: mma_slab<1, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        default: break;
+    }
+}
+
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding of simm16).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <bool LONG, int G, bool ARG, int BK, int NS, bool DMA>
 __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
-    __shared__ __attribute__((aligned(16))) uint8_t s_tile[2][2][FWD_TM * 128];   // [stage][A|B]
+    static_assert(BK == 64 || BK == 32, "slab depth");
+    static_assert(DMA || (BK == 64 && NS == 2), "register-staged loader is BK = 64, two stages");
+    constexpr int RB = BK * 2;               // bytes per tile row per slab
+    constexpr int CPR = RB / 16;             // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;            // rows covered by one wave-wide 16-byte-per-lane access
+    constexpr int IPW = FWD_TM / RPI / 8;    // such accesses per wave, operand and slab
+    constexpr int KS = BK / 16;              // MFMA k-steps per slab
+    constexpr int SLAB = FWD_TM * RB;        // bytes per operand per stage
+    constexpr int LPT = 2 * IPW;             // loads per thread per slab (A then B)
+
+    // One array per ring stage ([A|B][SLAB] each): distinct objects let the compiler see that a
+    // fragment read of one stage cannot alias a direct-to-LDS load into another, so it does not
+    // serialise them with a full vmcnt wait.  Stages beyond NS are never referenced and cost nothing.
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring0[2][SLAB];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring1[2][SLAB];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring2[2][SLAB];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring3[2][SLAB];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_pair[2][2][SLAB];    // register-staged loader only
+    auto ring = [&](auto st) -> uint8_t* {
+        constexpr int ST = decltype(st)::value;
+        if constexpr (ST == 0) return &s_ring0[0][0];
+        else if constexpr (ST == 1) return &s_ring1[0][0];
+        else if constexpr (ST == 2) return &s_ring2[0][0];
+        else return &s_ring3[0][0];
+    };
     __shared__ int s_rowtok[FWD_TM];     // row of H (b*S+s) feeding each tile row
     __shared__ int s_rowpos[FWD_TM];     // sequence position s of each tile row
     __shared__ float s_xm[4][2][32];
@@ -87,25 +167,32 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     const int half = lane >> 5;
     const int l32 = lane & 31;
     const int D = p.D;
-    const int nk = (D + FWD_BK - 1) / FWD_BK;
+    const int nk = (D + BK - 1) / BK;
 
-    // ---- loader geometry: thread -> (row ldr + 64 i, 16-byte chunk ldc) ----
-    const int ldc = tid & 7;
-    const int ldr = tid >> 3;
-    const int st_off = lds_off(ldr, ldc);           // + i * 64 * 128 (row & 7 unchanged)
-    const uint16_t* wptr[4];
+    // ---- loader geometry: access j of wave w covers tile rows (8 j + w) RPI .. + RPI, 1024 contiguous
+    //      LDS bytes; lane -> (row lrow, LDS chunk slot lp), which holds global chunk lp ^ swizzle(row) ----
+    const int lrow = wave * RPI + lane / CPR;                 // + 8 RPI j
+    const int lp = lane % CPR;
+    const int gch = lp ^ lds_swz<BK>(lrow);                   // swizzle bits do not depend on j
+    const int st_off = lrow * RB + lp * 16;                   // + 8192 j   (register-staged loader)
+    const uint16_t* wptr[IPW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int v = v0 + ldr + 64 * i;
+    for (int j = 0; j < IPW; ++j) {
+        int v = v0 + lrow + 8 * RPI * j;
         v = v < p.V ? v : p.V - 1;
-        wptr[i] = p.W + (size_t)v * D + ldc * 8;
+        wptr[j] = p.W + (size_t)v * D + gch * 8;
     }
     // ---- fragment geometry ----
-    const int fa_row = wm * 128 + l32;               // + 32 i
-    const int fb_row = wn * 64 + l32;                // + 32 c
-    int fsw[4];
+    // Row blocks of a wave: the long layout interleaves them between the two waves that share a SIMD
+    // (wave wm owns tile row blocks wm, wm+2, wm+4, wm+6) so that a short last chunk splits evenly;
+    // the short layout keeps them contiguous (4 wm .. 4 wm + 3): a sequence slot must not straddle waves.
+    const int fa_row = (LONG ? wm * 32 : wm * 128) + l32;
+    constexpr int A_STRIDE = (LONG ? 64 : 32) * RB;           // bytes between a wave's consecutive row blocks
+    constexpr int B_STRIDE = 32 * RB;
+    const int fb_row = wn * 64 + l32;
+    int fsw[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) fsw[ks] = (((ks * 2 + half) ^ l32) & 7) << 4;
+    for (int ks = 0; ks < KS; ++ks) fsw[ks] = ((ks * 2 + half) ^ lds_swz<BK>(l32)) << 4;
 
     int len_b = 0, b_long = 0, n_chunks = 1;
     if (LONG) {
@@ -125,6 +212,13 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     int run_s[2] = {0, 0};
 
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        // Row blocks (of 32 rows) that hold real tokens in this chunk; na = how many of them belong
+        // to this wave.  The others are not multiplied.
+        int na = 4;
+        if (LONG) {
+            const int rows = min(FWD_TM, len_b - chunk * FWD_TM);
+            na = (((rows + 31) >> 5) + 1 - wm) >> 1;
+        }
         // ---- which token feeds each tile row ----
         if (tid < FWD_TM) {
             int b, j, lb;
@@ -143,9 +237,9 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
             s_rowpos[tid] = s;
         }
         __syncthreads();
-        const uint16_t* hptr[4];
+        const uint16_t* hptr[IPW];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) hptr[i] = p.H + (size_t)s_rowtok[ldr + 64 * i] * D + ldc * 8;
+        for (int j = 0; j < IPW; ++j) hptr[j] = p.H + (size_t)s_rowtok[lrow + 8 * RPI * j] * D + gch * 8;
 
         floatx16 acc[4][2];
 #pragma unroll
@@ -155,57 +249,87 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][c][r] = 0.f;
 
-        uint4 ra[4], rb[4];
-        // K slabs are full except possibly the last one (D not a multiple of 64): only that one pays
-        // for per-chunk predication.
-        auto gload = [&](int kt) {
-            const int koff = kt * FWD_BK;
-            if (koff + FWD_BK <= D) {
+        if constexpr (DMA) {
+            // Slab kt goes to ring stage kt % NS.  Each wave-wide load fills 1024 contiguous LDS bytes
+            // (lane l lands at +16 l); the wave-uniform base goes through M0.
+            auto issue = [&](auto st, int kt) {
+                uint8_t* dst = ring(st) + wave * 1024;
+                const int koff = kt * BK;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    ra[i] = *reinterpret_cast<const uint4*>(hptr[i] + koff);
-                    rb[i] = *reinterpret_cast<const uint4*>(wptr[i] + koff);
+                for (int j = 0; j < IPW; ++j)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(hptr[j] + koff),
+                        (__attribute__((address_space(3))) void*)(dst + j * 8192), 16, 0, 0);
+#pragma unroll
+                for (int j = 0; j < IPW; ++j)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(wptr[j] + koff),
+                        (__attribute__((address_space(3))) void*)(dst + SLAB + j * 8192), 16, 0, 0);
+            };
+            // One pipeline step for slab kt, which lives in stage ST (compile-time so that every LDS
+            // access names its stage's array).
+            auto step = [&](auto st, int kt) {
+                constexpr int ST = decltype(st)::value;
+                // slabs after kt that are already in flight may stay in flight
+                const int ahead = min(nk - 1 - kt, NS - 2);
+                if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
+                else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
+                else wait_vmcnt<0>();
+                __syncthreads();        // slab kt has landed for every wave; stage (kt-1) % NS is free
+                if (kt + NS - 1 < nk) issue(std::integral_constant<int, (ST + NS - 1) % NS>{}, kt + NS - 1);
+                const uint8_t* sa = ring(st) + fa_row * RB;
+                const uint8_t* sb = ring(st) + SLAB + fb_row * RB;
+                mma_dispatch<4, KS>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc);
+            };
+            if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
+            if (NS > 2 && 1 < nk) issue(std::integral_constant<int, 1 % NS>{}, 1);
+            if (NS > 3 && 2 < nk) issue(std::integral_constant<int, 2 % NS>{}, 2);
+            for (int kt = 0; kt < nk; kt += NS) {
+                step(std::integral_constant<int, 0>{}, kt);
+                if (kt + 1 < nk) step(std::integral_constant<int, 1 % NS>{}, kt + 1);
+                if (NS > 2 && kt + 2 < nk) step(std::integral_constant<int, 2 % NS>{}, kt + 2);
+                if (NS > 3 && kt + 3 < nk) step(std::integral_constant<int, 3 % NS>{}, kt + 3);
+            }
+        } else {
+            uint4 ra[IPW], rb[IPW];
+            // K slabs are full except possibly the last one (D not a multiple of 64): only that one
+            // pays for per-chunk predication.
+            auto gload = [&](int kt) {
+                const int koff = kt * BK;
+                if (koff + BK <= D) {
+#pragma unroll
+                    for (int j = 0; j < IPW; ++j) {
+                        ra[j] = *reinterpret_cast<const uint4*>(hptr[j] + koff);
+                        rb[j] = *reinterpret_cast<const uint4*>(wptr[j] + koff);
+                    }
+                } else {
+                    const bool kval = koff + gch * 8 < D;
+#pragma unroll
+                    for (int j = 0; j < IPW; ++j) {
+                        ra[j] = kval ? *reinterpret_cast<const uint4*>(hptr[j] + koff) : make_uint4(0, 0, 0, 0);
+                        rb[j] = kval ? *reinterpret_cast<const uint4*>(wptr[j] + koff) : make_uint4(0, 0, 0, 0);
+                    }
                 }
-            } else {
-                const bool kval = koff + ldc * 8 < D;
+            };
+            auto lstore = [&](int st) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    ra[i] = kval ? *reinterpret_cast<const uint4*>(hptr[i] + koff) : make_uint4(0, 0, 0, 0);
-                    rb[i] = kval ? *reinterpret_cast<const uint4*>(wptr[i] + koff) : make_uint4(0, 0, 0, 0);
+                for (int j = 0; j < IPW; ++j) {
+                    *reinterpret_cast<uint4*>(&s_pair[st][0][st_off + j * 8192]) = ra[j];
+                    *reinterpret_cast<uint4*>(&s_pair[st][1][st_off + j * 8192]) = rb[j];
                 }
-            }
-        };
-        auto lstore = [&](int st) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                *reinterpret_cast<uint4*>(&s_tile[st][0][st_off + i * 64 * 128]) = ra[i];
-                *reinterpret_cast<uint4*>(&s_tile[st][1][st_off + i * 64 * 128]) = rb[i];
-            }
-        };
-
-        gload(0);
-        lstore(0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int st = kt & 1;
-            if (kt + 1 < nk) gload(kt + 1);
-            const uint8_t* sa = &s_tile[st][0][fa_row * 128];
-            const uint8_t* sb = &s_tile[st][1][fb_row * 128];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 fa[4], fb[2];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + fsw[ks]);
-#pragma unroll
-                for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * 32 * 128 + fsw[ks]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int c = 0; c < 2; ++c)
-                        acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
-            }
-            if (kt + 1 < nk) lstore(st ^ 1);
+            };
+            gload(0);
+            lstore(0);
             __syncthreads();
+            for (int kt = 0; kt < nk; ++kt) {
+                const int st = kt & 1;
+                if (kt + 1 < nk) gload(kt + 1);
+                const uint8_t* sa = &s_pair[st][0][fa_row * RB];
+                const uint8_t* sb = &s_pair[st][1][fb_row * RB];
+                mma_dispatch<4, KS>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc);
+                if (kt + 1 < nk) lstore(st ^ 1);
+                __syncthreads();
+            }
         }
 
         // ---- epilogue: in-lane max/argmax over each slot's rows ----
@@ -219,21 +343,24 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 m[c] = -INFINITY;
                 e[c] = 0;
 #pragma unroll
-                for (int i = q * G; i < q * G + G; ++i)
+                for (int i = q * G; i < q * G + G; ++i) {
+                    if (i < na) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float a = acc[i][c][r];
-                        if (ARG) {
-                            if (a > m[c]) { m[c] = a; e[c] = i * 16 + r; }
-                        } else {
-                            m[c] = fmaxf(m[c], a);
+                        for (int r = 0; r < 16; ++r) {
+                            const float a = acc[i][c][r];
+                            if (ARG) {
+                                if (a > m[c]) { m[c] = a; e[c] = i * 16 + r; }
+                            } else {
+                                m[c] = fmaxf(m[c], a);
+                            }
                         }
                     }
+                }
             }
             if (LONG) {
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    const int s = ARG ? s_rowpos[wm * 128 + acc_row(e[c], half)] : 0;
+                    const int s = ARG ? s_rowpos[acc_row<LONG>(e[c], half, wm)] : 0;
                     if (m[c] > run_m[c]) { run_m[c] = m[c]; run_s[c] = s; }
                 }
             } else {
@@ -242,7 +369,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 int ss[2];
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    int s = ARG ? s_rowpos[wm * 128 + acc_row(e[c], half)] : 0;
+                    int s = ARG ? s_rowpos[acc_row<LONG>(e[c], half, wm)] : 0;
                     const float mo = __shfl_xor(m[c], 32);
                     const int so = __shfl_xor(s, 32);
                     float mc = m[c];
@@ -263,7 +390,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 }
             }
         }
-        __syncthreads();     // the next chunk rewrites the row tables
+        __syncthreads();     // the next chunk rewrites the row tables and the ring
     }
 
     if (LONG) {

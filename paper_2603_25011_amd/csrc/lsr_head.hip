@@ -115,11 +115,21 @@ struct Prof {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : LSR_ERR_LAUNCH; }
 
+// Loader choice: direct-to-LDS ring when D is a multiple of the slab depth, else the register-staged
+// loader that can zero-fill the last slab.
+constexpr int FWD_DMA_BK = 64;
+constexpr int FWD_DMA_NS = 2;
+
 template <bool LONG, int G>
 void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
-    const int grid = (p.n_logical + 7) / 8 * 8;
-    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true>), dim3(grid), dim3(FWD_THREADS), 0, st, p);
-    else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false>), dim3(grid), dim3(FWD_THREADS), 0, st, p);
+    const dim3 grid((p.n_logical + 7) / 8 * 8), block(FWD_THREADS);
+    if (p.D % FWD_DMA_BK == 0) {
+        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, FWD_DMA_BK, FWD_DMA_NS, true>), grid, block, 0, st, p);
+        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, FWD_DMA_BK, FWD_DMA_NS, true>), grid, block, 0, st, p);
+    } else {
+        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, false>), grid, block, 0, st, p);
+        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, false>), grid, block, 0, st, p);
+    }
 }
 
 int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
