@@ -78,35 +78,95 @@ __device__ __forceinline__ int acc_row(int e, int half, int wm) {
     return blk * 32 + ((e & 15) >> 2) * 8 + half * 4 + (e & 3);
 }
 
-// One K slab of MFMAs for the first NA of this wave's four row blocks.
-template <int NA, int KS>
+// One K slab of MFMAs for the first NA of this wave's four row blocks.  With PF the fragments are
+// double buffered in registers: the reads for k-step ks+1 are issued before the MFMAs of k-step ks,
+// so the LDS latency (longer while direct-to-LDS writes are landing) hides behind NA*2 MFMAs.
+// NDMA direct-to-LDS loads of a later slab are issued from inside the MFMA stream, spread evenly
+// over the first SPREAD k-steps.  A burst of loads right after the barrier makes every wave sit in
+// the vector-memory issue queue (the address unit takes ~16 cycles per 1 KiB wave load) while the
+// MFMA pipe idles; interleaved, the pipe keeps running on the MFMAs already issued.
+template <int NA, int KS, bool PF, int NDMA, int SPREAD, typename DmaFn>
 __device__ __forceinline__ void mma_slab(const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
-                                         const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
+                                         const int (&fsw)[KS], floatx16 (&acc)[4][2], DmaFn&& dma) {
+    constexpr int M = NA * 2;                              // MFMAs per k-step
+    constexpr int Q = SPREAD > 0 ? NDMA / SPREAD : 0;      // loads per k-step while spreading
+    if constexpr (PF) {
+        bf16x8 fa[2][NA], fb[2][2];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 fa[NA], fb[2];
+        for (int c = 0; c < 2; ++c) fb[0][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[0]);
 #pragma unroll
-        for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks]);
+        for (int i = 0; i < NA; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[0]);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks]);
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KS) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
+                for (int c = 0; c < 2; ++c)
+                    fb[nxt][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks + 1]);
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
-                acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
+                for (int i = 0; i < NA; ++i)
+                    fa[nxt][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this k-step's MFMAs
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                acc[m >> 1][m & 1] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m >> 1], fb[cur][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
+                if (ks < SPREAD) {
+                    // after MFMA m the number of issued loads is topped up to ceil((m+1) Q / M)
+                    const int lo = (m * Q + M - 1) / M, hi = ((m + 1) * Q + M - 1) / M;
+#pragma unroll
+                    for (int t = lo; t < hi; ++t) dma(ks * Q + t);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 fa[NA], fb[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks]);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks]);
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
+        }
     }
 }
 
-template <int NA, int KS>
+template <int KS, bool PF, int NDMA, int SPREAD, typename DmaFn>
 __device__ __forceinline__ void mma_dispatch(int na, const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
-                                             const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
+                                             const int (&fsw)[KS], floatx16 (&acc)[4][2], DmaFn&& dma) {
     switch (na) {
-        case 4: mma_slab<4, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
-        case 3: mma_slab<3, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
-        case 2: mma_slab<2, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
-        case 1: mma_slab<1, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
-        default: break;
+        case 4: mma_slab<4, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
+        case 3: mma_slab<3, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
+        case 2: mma_slab<2, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
+        case 1: mma_slab<1, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
+        default:                                    // no live row block in this wave: only its loads
+#pragma unroll
+            for (int n = 0; n < NDMA; ++n) dma(n);
+            break;
     }
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
+// lds_base + 16 l (lds_base is wave-uniform and travels in M0).  Written as inline assembly on
+// purpose: when the compiler sees its own LDS-DMA builtin it stops using partial lgkmcnt waits for
+// every later LDS read, which serialises the fragment prefetch.  Completion is tracked by hand with
+// vmcnt (wait_vmcnt below) before the workgroup barrier that publishes the slab.
+__device__ __forceinline__ void dma16_to_lds(const void* gptr, uint32_t lds_base) {
+    // (an SALU write of M0 needs one wait state before an LDS-DMA instruction reads it)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));   // LDS aperture: low 32 bits are the offset
 }
 
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding of simm16).
@@ -115,7 +175,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <bool LONG, int G, bool ARG, int BK, int NS, bool DMA>
+template <bool LONG, int G, bool ARG, int BK, int NS, bool DMA, int SPREAD = BK / 32>
 __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     static_assert(BK == 64 || BK == 32, "slab depth");
     static_assert(DMA || (BK == 64 && NS == 2), "register-staged loader is BK = 64, two stages");
@@ -252,43 +312,61 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
         if constexpr (DMA) {
             // Slab kt goes to ring stage kt % NS.  Each wave-wide load fills 1024 contiguous LDS bytes
             // (lane l lands at +16 l); the wave-uniform base goes through M0.
-            auto issue = [&](auto st, int kt) {
-                uint8_t* dst = ring(st) + wave * 1024;
+            // load n (0 .. LPT-1) of slab kt into ring stage ST: first the A rows, then the B rows
+            auto issue_one = [&](auto st, int kt, int n) {
+                const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr(ring(st)) + wave * 1024);
                 const int koff = kt * BK;
-#pragma unroll
-                for (int j = 0; j < IPW; ++j)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(hptr[j] + koff),
-                        (__attribute__((address_space(3))) void*)(dst + j * 8192), 16, 0, 0);
-#pragma unroll
-                for (int j = 0; j < IPW; ++j)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(wptr[j] + koff),
-                        (__attribute__((address_space(3))) void*)(dst + SLAB + j * 8192), 16, 0, 0);
+                if (n < IPW) dma16_to_lds(hptr[n] + koff, dst + n * 8192);
+                else dma16_to_lds(wptr[n - IPW] + koff, dst + SLAB + (n - IPW) * 8192);
             };
-            // One pipeline step for slab kt, which lives in stage ST (compile-time so that every LDS
-            // access names its stage's array).
-            auto step = [&](auto st, int kt) {
-                constexpr int ST = decltype(st)::value;
-                // slabs after kt that are already in flight may stay in flight
-                const int ahead = min(nk - 1 - kt, NS - 2);
-                if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
-                else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
-                else wait_vmcnt<0>();
-                __syncthreads();        // slab kt has landed for every wave; stage (kt-1) % NS is free
-                if (kt + NS - 1 < nk) issue(std::integral_constant<int, (ST + NS - 1) % NS>{}, kt + NS - 1);
-                const uint8_t* sa = ring(st) + fa_row * RB;
-                const uint8_t* sb = ring(st) + SLAB + fb_row * RB;
-                mma_dispatch<4, KS>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc);
+            auto issue = [&](auto st, int kt) {
+#pragma unroll
+                for (int n = 0; n < LPT; ++n) issue_one(st, kt, n);
             };
-            if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
-            if (NS > 2 && 1 < nk) issue(std::integral_constant<int, 1 % NS>{}, 1);
-            if (NS > 3 && 2 < nk) issue(std::integral_constant<int, 2 % NS>{}, 2);
-            for (int kt = 0; kt < nk; kt += NS) {
-                step(std::integral_constant<int, 0>{}, kt);
-                if (kt + 1 < nk) step(std::integral_constant<int, 1 % NS>{}, kt + 1);
-                if (NS > 2 && kt + 2 < nk) step(std::integral_constant<int, 2 % NS>{}, kt + 2);
-                if (NS > 3 && kt + 3 < nk) step(std::integral_constant<int, 3 % NS>{}, kt + 3);
+            // The whole slab loop is instantiated once per count NA of live row blocks and the choice is
+            // made per chunk, outside the loop, so that each instance is straight-line MFMA code.
+            auto run_slabs = [&](auto na_c) {
+                constexpr int NA = decltype(na_c)::value;
+                // One pipeline step for slab kt, which lives in stage ST (compile-time so that every
+                // LDS access names its stage's array).  The loads of slab kt + NS - 1 ride inside its
+                // MFMA stream.
+                auto step = [&](auto st, int kt) {
+                    constexpr int ST = decltype(st)::value;
+                    // slabs after kt that are already in flight may stay in flight
+                    const int ahead = min(nk - 1 - kt, NS - 2);
+                    if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
+                    else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
+                    else wait_vmcnt<0>();
+                    __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
+                    const bool more = kt + NS - 1 < nk;
+                    auto dma = [&](int n) {
+                        if (more) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, kt + NS - 1, n);
+                    };
+                    if constexpr (NA == 0) {        // no live row block in this wave: only its loads
+#pragma unroll
+                        for (int n = 0; n < LPT; ++n) dma(n);
+                    } else {
+                        const uint8_t* sa = ring(st) + fa_row * RB;
+                        const uint8_t* sb = ring(st) + SLAB + fb_row * RB;
+                        mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
+                    }
+                };
+                if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
+                if (NS > 2 && 1 < nk) issue(std::integral_constant<int, 1 % NS>{}, 1);
+                if (NS > 3 && 2 < nk) issue(std::integral_constant<int, 2 % NS>{}, 2);
+                for (int kt = 0; kt < nk; kt += NS) {
+                    step(std::integral_constant<int, 0>{}, kt);
+                    if (kt + 1 < nk) step(std::integral_constant<int, 1 % NS>{}, kt + 1);
+                    if (NS > 2 && kt + 2 < nk) step(std::integral_constant<int, 2 % NS>{}, kt + 2);
+                    if (NS > 3 && kt + 3 < nk) step(std::integral_constant<int, 3 % NS>{}, kt + 3);
+                }
+            };
+            switch (na) {
+                case 4: run_slabs(std::integral_constant<int, 4>{}); break;
+                case 3: run_slabs(std::integral_constant<int, 3>{}); break;
+                case 2: run_slabs(std::integral_constant<int, 2>{}); break;
+                case 1: run_slabs(std::integral_constant<int, 1>{}); break;
+                default: run_slabs(std::integral_constant<int, 0>{}); break;
             }
         } else {
             uint4 ra[IPW], rb[IPW];
@@ -326,7 +404,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 if (kt + 1 < nk) gload(kt + 1);
                 const uint8_t* sa = &s_pair[st][0][fa_row * RB];
                 const uint8_t* sb = &s_pair[st][1][fb_row * RB];
-                mma_dispatch<4, KS>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc);
+                mma_dispatch<KS, false, 0, 0>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc, [](int) {});
                 if (kt + 1 < nk) lstore(st ^ 1);
                 __syncthreads();
             }
