@@ -7,6 +7,7 @@
 
 #include "bwd.hpp"
 #include "fwd_bf16.hpp"
+#include "fwd_bf16_persist.hpp"
 #include "fwd_misc.hpp"
 
 namespace {
@@ -35,12 +36,13 @@ int check_desc(const lsr_head_desc* d, Shape* out) {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// ---- forward workspace: len[B] | pos[B*S] ----
-struct FwdWs { size_t len_off, pos_off, total; };
+// ---- forward workspace: tile counters[8] | len[B] | pos[B*S] ----
+struct FwdWs { size_t ctr_off, len_off, pos_off, total; };
 FwdWs fwd_ws(const Shape& s) {
     FwdWs w;
-    w.len_off = 0;
-    w.pos_off = align_up(sizeof(int) * (size_t)s.B);
+    w.ctr_off = 0;
+    w.len_off = ALIGN;
+    w.pos_off = w.len_off + align_up(sizeof(int) * (size_t)s.B);
     w.total = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
     return w;
 }
@@ -69,15 +71,17 @@ BwdWs bwd_ws(const Shape& s) {
     return w;
 }
 
-int check_device() {
+int check_device(int* n_cus) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
-    static int ok_dev[64] = {0};
-    if (dev >= 0 && dev < 64 && ok_dev[dev]) return LSR_OK;
+    static int ok_dev[64] = {0};     // holds the CU count once a device has been checked
+    if (dev >= 0 && dev < 64 && ok_dev[dev]) { *n_cus = ok_dev[dev]; return LSR_OK; }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return LSR_ERR_ARCH;
-    if (dev >= 0 && dev < 64) ok_dev[dev] = 1;
+    if (prop.multiProcessorCount < 1) return LSR_ERR_ARCH;
+    *n_cus = prop.multiProcessorCount;
+    if (dev >= 0 && dev < 64) ok_dev[dev] = prop.multiProcessorCount;
     return LSR_OK;
 }
 
@@ -115,18 +119,22 @@ struct Prof {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : LSR_ERR_LAUNCH; }
 
-// Loader choice: direct-to-LDS ring when D is a multiple of the slab depth, else the register-staged
-// loader that can zero-fill the last slab.
-constexpr int FWD_DMA_BK = 64;
-constexpr int FWD_DMA_NS = 2;
-
+// Kernel choice: the persistent direct-to-LDS kernel when D is a multiple of the 64-wide K slab,
+// else the register-staged kernel that can zero-fill the last slab.
 template <bool LONG, int G>
-void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
-    const dim3 grid((p.n_logical + 7) / 8 * 8), block(FWD_THREADS);
-    if (p.D % FWD_DMA_BK == 0) {
-        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, FWD_DMA_BK, FWD_DMA_NS, true>), grid, block, 0, st, p);
-        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, FWD_DMA_BK, FWD_DMA_NS, true>), grid, block, 0, st, p);
+void launch_fwd_bf16(const FwdParams& p, int* tile_ctr, int n_cus, bool arg, hipStream_t st) {
+    const dim3 block(FWD_THREADS);
+    if (p.D % 64 == 0) {
+        FwdPersistParams pp;
+        pp.f = p;
+        pp.ctr = tile_ctr;
+        pp.n_tiles = p.n_vtiles * p.n_rowgroups;
+        pp.per_xcd = (pp.n_tiles + 7) / 8;
+        const dim3 grid(n_cus);             // one resident workgroup per CU; surplus ones exit at once
+        if (arg) hipLaunchKernelGGL((fwd_bf16_persistent_kernel<LONG, G, true>), grid, block, 0, st, pp);
+        else     hipLaunchKernelGGL((fwd_bf16_persistent_kernel<LONG, G, false>), grid, block, 0, st, pp);
     } else {
+        const dim3 grid((p.n_logical + 7) / 8 * 8);
         if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, false>), grid, block, 0, st, p);
         else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, false>), grid, block, 0, st, p);
     }
@@ -143,16 +151,18 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         return LSR_ERR_ALIGN;
     const FwdWs w = fwd_ws(s);
     if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
-    rc = check_device();
+    int n_cus = 0;
+    rc = check_device(&n_cus);
     if (rc != LSR_OK) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     prof.stream = st;
+    int* ctr = reinterpret_cast<int*>(static_cast<char*>(ws) + w.ctr_off);
     int* len = reinterpret_cast<int*>(static_cast<char*>(ws) + w.len_off);
     int* pos = reinterpret_cast<int*>(static_cast<char*>(ws) + w.pos_off);
 
     prof.begin(0);
-    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
+    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S, ctr);
     prof.end(0);
     if ((rc = launch_status()) != LSR_OK) return rc;
 
@@ -174,15 +184,15 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         if (s.S > 128) {
             p.n_rowgroups = s.B;
             p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            launch_fwd_bf16<true, 4>(p, I != nullptr, st);
+            launch_fwd_bf16<true, 4>(p, ctr, n_cus, I != nullptr, st);
         } else {
             const int G = s.S <= 32 ? 1 : (s.S <= 64 ? 2 : 4);
             const int spt = FWD_TM / (32 * G);
             p.n_rowgroups = (s.B + spt - 1) / spt;
             p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            if (G == 1) launch_fwd_bf16<false, 1>(p, I != nullptr, st);
-            else if (G == 2) launch_fwd_bf16<false, 2>(p, I != nullptr, st);
-            else launch_fwd_bf16<false, 4>(p, I != nullptr, st);
+            if (G == 1) launch_fwd_bf16<false, 1>(p, ctr, n_cus, I != nullptr, st);
+            else if (G == 2) launch_fwd_bf16<false, 2>(p, ctr, n_cus, I != nullptr, st);
+            else launch_fwd_bf16<false, 4>(p, ctr, n_cus, I != nullptr, st);
         }
     }
     prof.end(1);
@@ -226,7 +236,8 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     if (s.S > 8192 || s.B > 6144) return LSR_ERR_SHAPE;      // LDS tables of the bucket sort / dW staging
     const BwdWs w = bwd_ws(s);
     if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
-    rc = check_device();
+    int n_cus = 0;
+    rc = check_device(&n_cus);
     if (rc != LSR_OK) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
