@@ -10,17 +10,14 @@ constexpr int PREP_THREADS = 256;
 // One workgroup per sequence: len[b] = number of valid tokens, pos[b, 0..len) = their positions in
 // ascending order.  The attention mask M of Sec. 2 may be arbitrary, so this is a stream
 // compaction (ballot + popcount prefix), not a search for the first padding token.
-// Workgroup 0 also zeroes the eight tile counters of the persistent forward kernel.
 __global__ __launch_bounds__(PREP_THREADS) void fwd_prep_kernel(const uint8_t* __restrict__ mask,
                                                                  int* __restrict__ len,
-                                                                 int* __restrict__ pos, int S,
-                                                                 int* __restrict__ tile_ctr) {
+                                                                 int* __restrict__ pos, int S) {
     __shared__ int s_wave_total[PREP_THREADS / 64];
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    if (b == 0 && tid < 8) tile_ctr[tid] = 0;
     const uint8_t* mrow = mask + (size_t)b * S;
     int* prow = pos + (size_t)b * S;
     int base = 0;

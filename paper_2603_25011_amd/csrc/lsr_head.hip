@@ -7,7 +7,6 @@
 
 #include "bwd.hpp"
 #include "fwd_bf16.hpp"
-#include "fwd_bf16_persist.hpp"
 #include "fwd_misc.hpp"
 
 namespace {
@@ -36,12 +35,11 @@ int check_desc(const lsr_head_desc* d, Shape* out) {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// ---- forward workspace: tile counters[8] | len[B] | pos[B*S] ----
-struct FwdWs { size_t ctr_off, len_off, pos_off, total; };
+// ---- forward workspace: len[B] | pos[B*S] ----
+struct FwdWs { size_t len_off, pos_off, total; };
 FwdWs fwd_ws(const Shape& s) {
     FwdWs w;
-    w.ctr_off = 0;
-    w.len_off = ALIGN;
+    w.len_off = 0;
     w.pos_off = w.len_off + align_up(sizeof(int) * (size_t)s.B);
     w.total = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
     return w;
@@ -119,22 +117,15 @@ struct Prof {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : LSR_ERR_LAUNCH; }
 
-// Kernel choice: the persistent direct-to-LDS kernel when D is a multiple of the 64-wide K slab,
-// else the register-staged kernel that can zero-fill the last slab.
+// Loader choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab, else the
+// register-staged loader that can zero-fill the last slab.
 template <bool LONG, int G>
-void launch_fwd_bf16(const FwdParams& p, int* tile_ctr, int n_cus, bool arg, hipStream_t st) {
-    const dim3 block(FWD_THREADS);
+void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
+    const dim3 grid((p.n_logical + 7) / 8 * 8), block(FWD_THREADS);
     if (p.D % 64 == 0) {
-        FwdPersistParams pp;
-        pp.f = p;
-        pp.ctr = tile_ctr;
-        pp.n_tiles = p.n_vtiles * p.n_rowgroups;
-        pp.per_xcd = (pp.n_tiles + 7) / 8;
-        const dim3 grid(n_cus);             // one resident workgroup per CU; surplus ones exit at once
-        if (arg) hipLaunchKernelGGL((fwd_bf16_persistent_kernel<LONG, G, true>), grid, block, 0, st, pp);
-        else     hipLaunchKernelGGL((fwd_bf16_persistent_kernel<LONG, G, false>), grid, block, 0, st, pp);
+        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, true>), grid, block, 0, st, p);
+        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, true>), grid, block, 0, st, p);
     } else {
-        const dim3 grid((p.n_logical + 7) / 8 * 8);
         if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, false>), grid, block, 0, st, p);
         else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, false>), grid, block, 0, st, p);
     }
@@ -157,12 +148,11 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     prof.stream = st;
-    int* ctr = reinterpret_cast<int*>(static_cast<char*>(ws) + w.ctr_off);
     int* len = reinterpret_cast<int*>(static_cast<char*>(ws) + w.len_off);
     int* pos = reinterpret_cast<int*>(static_cast<char*>(ws) + w.pos_off);
 
     prof.begin(0);
-    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S, ctr);
+    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
     prof.end(0);
     if ((rc = launch_status()) != LSR_OK) return rc;
 
@@ -184,15 +174,15 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         if (s.S > 128) {
             p.n_rowgroups = s.B;
             p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            launch_fwd_bf16<true, 4>(p, ctr, n_cus, I != nullptr, st);
+            launch_fwd_bf16<true, 4>(p, I != nullptr, st);
         } else {
             const int G = s.S <= 32 ? 1 : (s.S <= 64 ? 2 : 4);
             const int spt = FWD_TM / (32 * G);
             p.n_rowgroups = (s.B + spt - 1) / spt;
             p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            if (G == 1) launch_fwd_bf16<false, 1>(p, ctr, n_cus, I != nullptr, st);
-            else if (G == 2) launch_fwd_bf16<false, 2>(p, ctr, n_cus, I != nullptr, st);
-            else launch_fwd_bf16<false, 4>(p, ctr, n_cus, I != nullptr, st);
+            if (G == 1) launch_fwd_bf16<false, 1>(p, I != nullptr, st);
+            else if (G == 2) launch_fwd_bf16<false, 2>(p, I != nullptr, st);
+            else launch_fwd_bf16<false, 4>(p, I != nullptr, st);
         }
     }
     prof.end(1);
