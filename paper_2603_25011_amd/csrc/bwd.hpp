@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
                                                        const int* __restrict__ I,
                                                        const int* __restrict__ cnt,
                                                        const int* __restrict__ bstart,
-                                                       int* __restrict__ perm_v, float* __restrict__ perm_g,
+                                                       uint2* __restrict__ perm,
                                                        int S, int V, int n_seg, int seg_len, int key_bits) {
     extern __shared__ int s_off[];          // [S] next free slot of each bucket
     const int seg = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
@@ -129,14 +129,23 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
     const int vend = min(V, vbeg + seg_len);
     const size_t row = (size_t)b * V;
     const unsigned long long lt = (1ull << lane) - 1ull;
+    // the next 64 entries are requested before the current ones are ranked (the ranking has two
+    // barriers and would otherwise expose a full memory latency per step)
+    float n_dy = 0.f, n_y = 0.f;
+    int n_i = 0;
+    auto request = [&](int base) {
+        const int v = base + lane;
+        const bool ok = v < vend;
+        n_dy = ok ? dY[row + v] : 0.f;
+        n_y = ok ? Y[row + v] : 0.f;
+        n_i = ok ? I[row + v] : 0;
+    };
+    request(vbeg);
     for (int base = vbeg; base < vend; base += 64) {
         const int v = base + lane;
-        float g = 0.f;
-        int key = 0;
-        if (v < vend) {
-            g = gate_grad(dY[row + v], Y[row + v]);
-            key = clamp_pos(I[row + v], S);
-        }
+        const float g = gate_grad(n_dy, n_y);      // 0 for lanes past the end (dy = 0, y = 0)
+        const int key = clamp_pos(n_i, S);
+        request(base + 64);
         const bool active = g != 0.f;
         unsigned long long same = __ballot(active);
         for (int bit = 0; bit < key_bits; ++bit) {
@@ -149,12 +158,14 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
         int dest = 0;
         if (active) {
             dest = s_off[key] + rank;
-            perm_v[row + dest] = v;
-            perm_g[row + dest] = g;
+            perm[row + dest] = make_uint2((unsigned)v, __float_as_uint(g));      // one 8-byte scattered store
         }
-        __syncthreads();
+        // The workgroup is a single wave: its LDS instructions execute in program order for all lanes,
+        // so the read of s_off above precedes this update and the update precedes the next step's
+        // read.  wave_barrier only pins that order for the compiler; no hardware barrier is needed.
+        __builtin_amdgcn_wave_barrier();
         if (active && rank == group - 1) s_off[key] = dest + 1;
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -164,8 +175,7 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
 template <typename T, int CPT>
 __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict__ W,
                                                              const int* __restrict__ bstart,
-                                                             const int* __restrict__ perm_v,
-                                                             const float* __restrict__ perm_g,
+                                                             const uint2* __restrict__ perm,
                                                              float* __restrict__ dH,
                                                              int S, int D, int V) {
     constexpr int N = RowChunk<T>::N;
@@ -184,8 +194,9 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict
 
     for (int base = beg; base < end; base += ROW_THREADS) {
         const int n = min(ROW_THREADS, end - base);
-        s_v[tid] = tid < n ? perm_v[prow + base + tid] : 0;     // padding: row 0 with weight 0
-        s_g[tid] = tid < n ? perm_g[prow + base + tid] : 0.f;
+        const uint2 ent = tid < n ? perm[prow + base + tid] : make_uint2(0u, 0u);   // padding: row 0, weight 0
+        s_v[tid] = (int)ent.x;
+        s_g[tid] = __uint_as_float(ent.y);
         __syncthreads();
         for (int k = 0; k < n; k += 4) {
             uint4 x[4][CPT];
@@ -314,6 +325,182 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
             for (int o = 32; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o);
             if (tid == 0) db[v] = gsum;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dW/db, column-sliced variant (D a multiple of 64).
+// The gathers of the kernel above hit rows of H scattered over all of H (tens of MB), so they are
+// served by the memory-side cache at a fraction of the L2 rate.  Here the work is cut into slices of
+// 64 hidden-state columns and the grid is ordered slice-major: the workgroups resident at any time
+// all gather from the same [tokens x 64] slice of H (a few MB at most), which stays in every XCD's
+// L2 (the host sizes a group of NDC consecutive slices to about 3 MiB of H and a workgroup walks the
+// slices of its group, so that the (g, I) staging is not repeated more often than needed).
+// A row piece is 64 elements = LPR lanes x 16 bytes; a wave therefore serves 64/LPR vocabulary
+// rows at once, walks b = 0..B-1 for them with eight gathers in flight per lane, and writes one
+// 64-column piece of each dW row.  Summation order over b is fixed.
+// dynamic LDS: B*VT floats + B*VT ints.   grid = ceil(V/VT) * ceil((D/64)/NDC).
+// ---------------------------------------------------------------------------------------------
+constexpr int DWS_COLS = 64;
+
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict__ H,
+                                                            const float* __restrict__ dY,
+                                                            const float* __restrict__ Y,
+                                                            const int* __restrict__ I,
+                                                            float* __restrict__ dW, float* __restrict__ db,
+                                                            int B, int S, int D, int V, int VT, int n_vtiles, int NDC) {
+    constexpr int N = RowChunk<T>::N;          // elements per 16-byte chunk
+    constexpr int LPR = DWS_COLS / N;          // lanes per row piece
+    constexpr int VPG = 64 / LPR;              // vocabulary rows a wave serves at once
+    extern __shared__ int s_dyn[];
+    float* s_g = reinterpret_cast<float*>(s_dyn);          // [B][VT]
+    int* s_i = s_dyn + (size_t)B * VT;                     // [B][VT]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int dg = blockIdx.x / n_vtiles;                  // slice-group-major order
+    const int v0 = (blockIdx.x - dg * n_vtiles) * VT;
+    const int dc_begin = dg * NDC;
+    const int dc_end = min(D / DWS_COLS, dc_begin + NDC);
+
+    // staging, four independent (dY, Y, I) triples in flight per thread
+    for (int e0 = tid; e0 < B * VT; e0 += 4 * blockDim.x) {
+        float dy[4], y[4];
+        int ix[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * blockDim.x;
+            const int bb = e / VT, vv = e - bb * VT;
+            const bool ok = e < B * VT && v0 + vv < V;
+            const size_t o = ok ? (size_t)bb * V + v0 + vv : 0;
+            dy[u] = ok ? dY[o] : 0.f;
+            y[u] = ok ? Y[o] : 0.f;
+            ix[u] = ok ? I[o] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * blockDim.x;
+            if (e < B * VT) {
+                s_g[e] = gate_grad(dy[u], y[u]);
+                s_i[e] = clamp_pos(ix[u], S);
+            }
+        }
+    }
+    __syncthreads();
+
+    if (db && dg == 0 && tid < VT && v0 + tid < V) {           // fixed-order sum over b
+        float sum = 0.f;
+        for (int b = 0; b < B; ++b) sum += s_g[b * VT + tid];
+        db[v0 + tid] = sum;
+    }
+    if (!dW) return;
+
+    for (int dc = dc_begin; dc < dc_end; ++dc) {
+        const int col0 = dc * DWS_COLS + (lane % LPR) * N;
+        for (int grp = wave; grp * VPG < VT; grp += n_waves) {
+            const int vv = grp * VPG + lane / LPR;
+            const int v = v0 + vv;
+            float acc[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[i] = 0.f;
+            for (int b0 = 0; b0 < B; b0 += 8) {
+                float g[8];
+                uint4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int b = b0 + u;
+                    g[u] = b < B ? s_g[b * VT + vv] : 0.f;
+                    x[u] = make_uint4(0, 0, 0, 0);
+                    if (g[u] != 0.f) {                           // only lanes with a contribution fetch
+                        const int idx = s_i[b * VT + vv];
+                        x[u] = *reinterpret_cast<const uint4*>(H + ((size_t)b * S + idx) * D + col0);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) RowChunk<T>::fma(x[u], g[u], acc);
+            }
+            if (v < V) {
+                float* out = dW + (size_t)v * D + col0;
+#pragma unroll
+                for (int i = 0; i < N; i += 4)
+                    *reinterpret_cast<float4*>(out + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dH, column-sliced variant (D a multiple of 64).
+// Buckets are sorted by v, and buckets that run at the same time walk the vocabulary at the same
+// pace, so at any moment the chip gathers rows of W from a moving window of the vocabulary.  With
+// whole rows that window is tens of MB (memory-side cache or HBM); cut into 64-column slices, with
+// the grid ordered slice-major, it is a few MB and lives in L2.  One wave owns one bucket and one
+// slice: a 64-column piece of a row is LPR lanes x 16 bytes, so the wave gathers 64/LPR bucket
+// entries per load, keeps four loads in flight per lane, and folds the per-entry partial sums with
+// a fixed butterfly at the end (reproducible order).   grid = ceil(B*S/4) * (D/64), 256 threads.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict__ W,
+                                                            const int* __restrict__ bstart,
+                                                            const uint2* __restrict__ perm,
+                                                            float* __restrict__ dH,
+                                                            int B, int S, int D, int V, int n_groups) {
+    constexpr int N = RowChunk<T>::N;
+    constexpr int LPR = DWS_COLS / N;          // lanes per row piece
+    constexpr int EPW = 64 / LPR;              // bucket entries a wave gathers per load
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int dc = blockIdx.x / n_groups;                          // slice-major order
+    const int bucket = (blockIdx.x - dc * n_groups) * 4 + wave;    // = b*S + s
+    if (bucket >= B * S) return;
+    const int b = bucket / S, s = bucket - b * S;
+    const int beg = bstart[(size_t)b * (S + 1) + s];
+    const int end = bstart[(size_t)b * (S + 1) + s + 1];
+    const size_t prow = (size_t)b * V;
+    const int col0 = dc * DWS_COLS + (lane % LPR) * N;
+    const int sub = lane / LPR;
+    float acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    // the (v, g) entries of the next four loads are fetched while the current rows are in flight, so
+    // the list read and the row gather it feeds never sit in one dependency chain
+    int nv[4];
+    float ng[4];
+    auto fetch_entries = [&](int base) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = base + u * EPW + sub;
+            const bool ok = k < end;
+            const uint2 ent = ok ? perm[prow + k] : make_uint2(0u, 0u);
+            nv[u] = (int)ent.x;
+            ng[u] = __uint_as_float(ent.y);
+        }
+    };
+    fetch_entries(beg);
+    for (int base = beg; base < end; base += 4 * EPW) {
+        float g[4];
+        uint4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            g[u] = ng[u];
+            x[u] = make_uint4(0, 0, 0, 0);
+            if (g[u] != 0.f) x[u] = *reinterpret_cast<const uint4*>(W + (size_t)nv[u] * D + col0);
+        }
+        fetch_entries(base + 4 * EPW);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) RowChunk<T>::fma(x[u], g[u], acc);
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += __shfl_xor(acc[i], off);
+    if (sub == 0) {
+        float* out = dH + (size_t)bucket * D + col0;
+#pragma unroll
+        for (int i = 0; i < N; i += 4)
+            *reinterpret_cast<float4*>(out + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
     }
 }
 

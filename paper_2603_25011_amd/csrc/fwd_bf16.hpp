@@ -44,7 +44,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int FWD_TM = 256;        // tile rows (tokens)
 constexpr int FWD_TN = 256;        // tile columns (vocabulary entries)
 constexpr int FWD_THREADS = 512;
-constexpr int FWD_GV = 4;          // vocabulary tiles per L2-sharing group
+#ifndef LSR_FWD_GV
+#define LSR_FWD_GV 4
+#endif
+constexpr int FWD_GV = LSR_FWD_GV;   // vocabulary tiles per L2-sharing group
 
 struct FwdParams {
     const uint16_t* H;

@@ -45,8 +45,8 @@ FwdWs fwd_ws(const Shape& s) {
     return w;
 }
 
-// ---- backward workspace: perm_v[B*V] | perm_g[B*V] | cnt[B*n_seg*S] | bstart[B*(S+1)] ----
-struct BwdWs { int n_seg, seg_len, key_bits; size_t pv_off, pg_off, cnt_off, bs_off, total; };
+// ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] ----
+struct BwdWs { int n_seg, seg_len, key_bits; size_t perm_off, cnt_off, bs_off, total; };
 BwdWs bwd_ws(const Shape& s) {
     BwdWs w;
     // enough (b, segment) waves to fill the chip, segments of at least 512 entries, and a count
@@ -61,9 +61,8 @@ BwdWs bwd_ws(const Shape& s) {
     w.key_bits = 0;
     while ((1 << w.key_bits) < s.S) ++w.key_bits;
     const size_t bv = (size_t)s.B * s.V;
-    w.pv_off = 0;
-    w.pg_off = w.pv_off + align_up(sizeof(int) * bv);
-    w.cnt_off = w.pg_off + align_up(sizeof(float) * bv);
+    w.perm_off = 0;
+    w.cnt_off = w.perm_off + align_up(sizeof(uint2) * bv);
     w.bs_off = w.cnt_off + align_up(sizeof(int) * (size_t)s.B * w.n_seg * s.S);
     w.total = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
     return w;
@@ -190,14 +189,14 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
 }
 
 template <typename T>
-void launch_dh(int cpt, dim3 grid, hipStream_t st, const T* W, const int* bstart, const int* pv, const float* pg,
+void launch_dh(int cpt, dim3 grid, hipStream_t st, const T* W, const int* bstart, const uint2* pm,
                float* dH, int S, int D, int V) {
     switch (cpt) {
-        case 1: hipLaunchKernelGGL((bwd_dh_kernel<T, 1>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
-        case 2: hipLaunchKernelGGL((bwd_dh_kernel<T, 2>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
-        case 4: hipLaunchKernelGGL((bwd_dh_kernel<T, 4>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
-        case 8: hipLaunchKernelGGL((bwd_dh_kernel<T, 8>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
-        default: hipLaunchKernelGGL((bwd_dh_kernel<T, 16>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pv, pg, dH, S, D, V); break;
+        case 1: hipLaunchKernelGGL((bwd_dh_kernel<T, 1>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
+        case 2: hipLaunchKernelGGL((bwd_dh_kernel<T, 2>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
+        case 4: hipLaunchKernelGGL((bwd_dh_kernel<T, 4>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
+        case 8: hipLaunchKernelGGL((bwd_dh_kernel<T, 8>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
+        default: hipLaunchKernelGGL((bwd_dh_kernel<T, 16>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
     }
 }
 
@@ -233,8 +232,7 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     prof.stream = st;
     char* base = static_cast<char*>(ws);
-    int* perm_v = reinterpret_cast<int*>(base + w.pv_off);
-    float* perm_g = reinterpret_cast<float*>(base + w.pg_off);
+    uint2* perm = reinterpret_cast<uint2*>(base + w.perm_off);
     int* cnt = reinterpret_cast<int*>(base + w.cnt_off);
     int* bstart = reinterpret_cast<int*>(base + w.bs_off);
 
@@ -254,27 +252,64 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
         prof.end(1);
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(2);
-        hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm_v, perm_g,
+        hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
                            s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
         prof.end(2);
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(3);
-        const dim3 grid(s.S, s.B);
-        if (s.dtype == LSR_F32) launch_dh<float>(cpt, grid, st, static_cast<const float*>(W), bstart, perm_v, perm_g, dH, s.S, s.D, s.V);
-        else launch_dh<uint16_t>(cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm_v, perm_g, dH, s.S, s.D, s.V);
+        if (s.D % DWS_COLS == 0) {
+            // column-sliced gathers: the moving window of W rows stays in L2
+            const int n_groups = (s.B * s.S + 3) / 4;
+            const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
+            if (s.dtype == LSR_F32)
+                hipLaunchKernelGGL((bwd_dh_sliced_kernel<float>), grid, dim3(256), 0, st, static_cast<const float*>(W), bstart,
+                                   perm, dH, s.B, s.S, s.D, s.V, n_groups);
+            else
+                hipLaunchKernelGGL((bwd_dh_sliced_kernel<uint16_t>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(W),
+                                   bstart, perm, dH, s.B, s.S, s.D, s.V, n_groups);
+        } else {
+            const dim3 grid(s.S, s.B);
+            if (s.dtype == LSR_F32) launch_dh<float>(cpt, grid, st, static_cast<const float*>(W), bstart, perm, dH, s.S, s.D, s.V);
+            else launch_dh<uint16_t>(cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm, dH, s.S, s.D, s.V);
+        }
         prof.end(3);
         if ((rc = launch_status()) != LSR_OK) return rc;
     }
     if (dW || db) {
-        // rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
-        int VT = 32;
-        while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
-        if ((size_t)s.B * VT * 8 > 48 * 1024) return LSR_ERR_SHAPE;    // B > 6144
-        const size_t lds = (size_t)s.B * VT * 8;
-        const dim3 grid((s.V + VT - 1) / VT);
         prof.begin(4);
-        if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
-        else launch_dw<uint16_t>(cpt, grid, lds, st, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+        // column-sliced gathers (L2-resident slices of H) need D % 64 == 0 and pay off while the (g, I)
+        // staging tile (at most 48 KiB) is at least 32 vocabulary rows wide, i.e. B <= 192: four waves
+        // per workgroup and enough workgroups per CU to hide the gather latency.  Larger batches of
+        // (then usually short) sequences keep the whole-row kernel, which compacts zero gradients.
+        int VT = 64;
+        while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
+        const int vpg = s.dtype == LSR_F32 ? 4 : 8;
+        if (s.D % DWS_COLS == 0 && VT >= 32) {
+            int waves = VT / vpg;
+            waves = waves < 1 ? 1 : (waves > 4 ? 4 : waves);
+            const size_t lds = (size_t)s.B * VT * 8;
+            const int n_vtiles = (s.V + VT - 1) / VT;
+            // slices per group: about 3 MiB of H rows (B*S rows x 64 columns each) stay L2-resident
+            const int n_dc = s.D / DWS_COLS;
+            const size_t slice_bytes = (size_t)s.B * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
+            int NDC = (int)((size_t)(3u << 20) / slice_bytes);
+            NDC = NDC < 1 ? 1 : (NDC > n_dc ? n_dc : NDC);
+            const int n_groups = (n_dc + NDC - 1) / NDC;
+            const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
+            if (s.dtype == LSR_F32)
+                hipLaunchKernelGGL((bwd_dw_sliced_kernel<float>), grid, block, lds, st, static_cast<const float*>(H), dY, Y, I,
+                                   dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
+            else
+                hipLaunchKernelGGL((bwd_dw_sliced_kernel<uint16_t>), grid, block, lds, st, static_cast<const uint16_t*>(H), dY,
+                                   Y, I, dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
+        } else {
+            // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows
+            VT = VT > 32 ? 32 : VT;
+            const size_t lds = (size_t)s.B * VT * 8;
+            const dim3 grid((s.V + VT - 1) / VT);
+            if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+            else launch_dw<uint16_t>(cpt, grid, lds, st, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+        }
         prof.end(4);
         if ((rc = launch_status()) != LSR_OK) return rc;
     }
