@@ -21,6 +21,13 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
+# Bytes the fused forward kernel moves between L2 and the memory fabric per launch, from rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs of this same script (summaries: profiles/c5_hbm_counters.txt).
+# FETCH_SIZE is scaled by 2.00 and WRITE_SIZE by 1.00, the factors a 1 GiB copy gives (--calib-copy).
+MEASURED_FWD_TRAFFIC_BYTES = {
+    "c5_large_fwdbwd": int((6393116 * 2.00 + 125743 * 1.00) * 1024),
+}
+
 
 def flops_forward(inp):
     w = inp.workload
@@ -55,8 +62,10 @@ def time_workload(name, steps, warmup, torch, wl, DeviceHead, profile=True):
     t1 = time.perf_counter()
     peak_bytes = torch.cuda.max_memory_allocated()
     ms_step = (t1 - t0) * 1e3 / steps
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps if do_bwd else 0.0
+    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev) if do_bwd else [0.0]
+    fwd_ms = sum(fwd_all) / steps
+    bwd_ms = sum(bwd_all) / len(bwd_all)
 
     nnz = 0
     if do_bwd:
@@ -66,9 +75,11 @@ def time_workload(name, steps, warmup, torch, wl, DeviceHead, profile=True):
     res = {
         "workload": name, "B": w.B, "S": w.S, "D": w.D, "V": w.V, "sum_len": inp.sum_len, "nnz": nnz,
         "ms_per_step": ms_step, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "fwd_ms_median": fwd_all[len(fwd_all) // 2], "fwd_ms_min": fwd_all[0],
+        "bwd_ms_median": bwd_all[len(bwd_all) // 2], "bwd_ms_min": bwd_all[0],
         "tflops_step": (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12,
         "fwd_tflops_valid": f_fwd / (fwd_ms * 1e-3) / 1e12,
-        "fwd_tflops_dense": 2.0 * w.B * w.S * w.D * w.V / (fwd_ms * 1e-3) / 1e12,
+        "fwd_tflops_dense_equivalent": 2.0 * w.B * w.S * w.D * w.V / (fwd_ms * 1e-3) / 1e12,
         "fwd_frac_mfma_peak": f_fwd / (fwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "peak_hbm_bytes": int(peak_bytes),
         "logits_avoided_bytes_bf16": int(2 * w.B * w.S * w.V),
@@ -152,8 +163,11 @@ def main():
     fwd_flops = flops_forward(inp)
     roof = {"bound": "mfma", "kernel": "fwd_bf16_kernel (fused GEMM + max/argmax + activation)",
             "achieved": fwd_flops / (res["fwd_ms"] * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "traffic": None, "flops_per_launch": fwd_flops, "avg_launch_ms": res["fwd_ms"],
-            "dense_tflops": res["fwd_tflops_dense"]}
+            "traffic": MEASURED_FWD_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per launch",
+            "algorithmic_bytes": int(w.B * w.S * w.D * 2 + w.V * w.D * 2 + w.B * w.V * 8 + w.V * 4),
+            "flops_per_launch": fwd_flops, "avg_launch_ms": res["fwd_ms"],
+            "note": "flops count valid tokens only; the launch time is the forward call "
+                    "(mask compaction, ~4 us, + the fused kernel) from events on the launch stream"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     del head
     torch.cuda.empty_cache()
@@ -178,13 +192,14 @@ def main():
         torch.cuda.synchronize()
 
     out = {
-        "metric": "fused LM-head fwd+bwd TFLOP/s (valid-token flops) and % MFMA peak; peak HBM bytes",
+        "metric": "fused LM-head fwd+bwd TFLOP/s and % MFMA peak; peak HBM bytes, |V|=30k/250k",
         "value": res["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={w.B} S={w.S} D={w.D} V={w.V}, valid lengths {w.len_lo}..{w.len_hi}, "
-                               f"forward+backward" if w.backward else f"{args.workload}: forward only",
-                   "sum_len": inp.sum_len, "nnz": res["nnz"]},
+                               + ("forward+backward" if w.backward else "forward only"),
+                   "sum_len": inp.sum_len, "nnz": res["nnz"], "flops": "valid tokens only: 2*sum_len*D*V + 4*nnz*D",
+                   "peak_hbm_bytes": res["peak_hbm_bytes"]},
         "roofline": roof,
         "cpu_baseline": cpu,
         "detail": res,
