@@ -9,8 +9,8 @@
 // wave (wm, wn) owns four 32-row blocks x columns [64 wn, 64 wn + 64), i.e. 4 x 2 blocks of the
 // 32x32x16 bf16 MFMA.  Tokens are the MFMA's row dimension: in the 32x32 accumulator layout a lane
 // holds 16 rows of ONE column, so the max over tokens starts as a plain in-lane reduction, is
-// finished with one exchange between the two half-waves, and (long layout) one exchange through
-// LDS between the two waves that share the columns.
+// finished with one exchange between the two half-waves; what is left per tile is one value per
+// (block, column), which goes through LDS to the scan that joins the blocks of a sequence.
 //
 // Operand staging.  K (the hidden size D) is walked in slabs of BK elements through an NS-stage
 // ring of LDS tiles.  Two loaders:
@@ -20,16 +20,20 @@
 //                 is a multiple of 8 (the last slab is zero-filled).
 // Rows are XOR-swizzled inside a slab so that the 16-byte fragment reads are bank-conflict free.
 //
-// Masking.  Only valid tokens are multiplied: a compaction pass lists the valid positions of every
-// sequence, and tile rows are gathered through that list.  Rows past the end of a sequence repeat
-// its last valid token, which cannot change a maximum or its lowest-index arg-max, so the
-// epilogue needs no per-element mask.  Whole 32-row blocks past the end are not multiplied at all.
+// Masking and packing.  Only valid tokens are multiplied.  A compaction pass lists the valid
+// positions of every sequence; each sequence is then cut into blocks of 32 rows (the MFMA's row
+// block), the last block padded with repeats of the sequence's last valid token, which cannot change
+// a maximum or its lowest-position arg-max.  The blocks of all sequences form one dense list, and a
+// tile is any 8 consecutive blocks of it, so tiles are full whatever the length mix; a block never
+// mixes two sequences, which keeps the first reduction step (in-lane over a lane's 16 rows of one
+// block) free of masks.
 //
-// Two row layouts, chosen on the host from S alone:
-//   long  (S > 128): a workgroup owns one sequence and walks its valid tokens in chunks of 256
-//                    rows, keeping a running (max, position) per column in registers.
-//   short (S <= 128): every sequence gets a fixed slot of G = 1, 2 or 4 row blocks (32 G >= S);
-//                    a tile holds 8/G sequences and each wave reduces its own slots.
+// Row groups.  The block list is cut into n_rowgroups contiguous ranges of whole sequences with
+// about the same number of blocks.  A workgroup owns (row group, vocabulary tile) and walks the
+// group's tiles; per tile it reduces every block to one (max, position) per column, and a scan over
+// the tile's blocks carries the running pair of the sequence that is still open in registers from
+// block to block and from tile to tile (the streaming reduction of Sec. 3).  The block that ends a
+// sequence triggers bias + ReLU + log1p and the store of Y and I.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -49,18 +53,24 @@ constexpr int FWD_THREADS = 512;
 #endif
 constexpr int FWD_GV = LSR_FWD_GV;   // vocabulary tiles per L2-sharing group
 
+constexpr int FWD_BLK = 32;                      // rows per block
+constexpr int FWD_TB = FWD_TM / FWD_BLK;         // blocks per tile
+constexpr int FWD_META_LAST = 1 << 31;           // block ends its sequence
+constexpr int FWD_META_EMPTY = 1 << 30;          // the sequence has no valid token
+
 struct FwdParams {
     const uint16_t* H;
     const uint16_t* W;
     const float* bias;
-    const int* len;      // [B]   number of valid tokens per sequence
-    const int* pos;      // [B,S] valid positions, ascending, first len[b] entries used
+    const int2* rows;        // [n_blocks * 32] per packed row: (row of H = b*S + s, position s)
+    const int* blk_meta;     // [n_blocks] sequence index b, ORed with FWD_META_LAST / FWD_META_EMPTY
+    const int* grp_blk0;     // [n_rowgroups + 1] first block of every row group
     float* Y;
-    int* I;              // may be null
+    int* I;                  // may be null
     int B, S, D, V;
-    int n_vtiles;        // ceil(V / 256)
-    int n_rowgroups;     // long: B; short: ceil(B / (8/G))
-    int n_logical;       // ceil(n_vtiles / GV) * GV * n_rowgroups
+    int n_vtiles;            // ceil(V / 256)
+    int n_rowgroups;
+    int n_logical;           // ceil(n_vtiles / GV) * GV * n_rowgroups
 };
 
 // Swizzle of the 16-byte chunk index inside a tile row.  A fragment read has lanes 0..31 on 32
@@ -73,17 +83,15 @@ __device__ __forceinline__ int lds_swz(int r) {
     return BK == 64 ? (r >> 1) & 7 : (r >> 2) & 3;
 }
 
-// Tile row of accumulator element e = 16*i + reg (i = the wave's i-th row block) for a lane in the
-// given half-wave: MFMA 32x32 output register r of lane l is row 8*(r/4) + 4*(l/32) + r%4 of its block.
-template <bool LONG>
-__device__ __forceinline__ int acc_row(int e, int half, int wm) {
-    const int blk = LONG ? 2 * (e >> 4) + wm : 4 * wm + (e >> 4);
-    return blk * 32 + ((e & 15) >> 2) * 8 + half * 4 + (e & 3);
+// Tile row of accumulator register r (0..15) of a lane in the given half-wave, in tile block blk:
+// MFMA 32x32 output register r of lane l is row 8*(r/4) + 4*(l/32) + r%4 of its block.
+__device__ __forceinline__ int acc_row(int blk, int r, int half) {
+    return blk * FWD_BLK + (r >> 2) * 8 + half * 4 + (r & 3);
 }
 
 // One K slab of MFMAs for the first NA of this wave's four row blocks.  With PF the fragments are
-// double buffered in registers: the reads for k-step ks+1 are issued before the MFMAs of k-step ks,
-// so the LDS latency (longer while direct-to-LDS writes are landing) hides behind NA*2 MFMAs.
+// double buffered in registers: the reads for k-step ks+1 are issued during the MFMAs of k-step ks,
+// so the LDS latency (longer while direct-to-LDS writes are landing) hides behind them.
 // NDMA direct-to-LDS loads of a later slab are issued from inside the MFMA stream, spread evenly
 // over the first SPREAD k-steps.  A burst of loads right after the barrier makes every wave sit in
 // the vector-memory issue queue (the address unit takes ~16 cycles per 1 KiB wave load) while the
@@ -102,27 +110,38 @@ __device__ __forceinline__ void mma_slab(const uint8_t* sa, int a_stride, const 
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KS) {
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-                    fb[nxt][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks + 1]);
-#pragma unroll
-                for (int i = 0; i < NA; ++i)
-                    fa[nxt][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks + 1]);
-            }
-            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this k-step's MFMAs
+            // Fragment read q of the next k-step, in the order its MFMAs consume them:
+            // B0, A0, B1, A1, A2, ...  One read is issued behind each MFMA of this k-step, not as a
+            // burst: both waves of a SIMD leave the barrier in phase, and while they both sit in a
+            // burst of LDS reads nobody feeds the matrix pipe.
+            auto read_next = [&](int q) {
+                if (ks + 1 < KS && q < NA + 2) {
+                    if (q == 0 || q == 2) {
+                        const int c = q >> 1;
+                        fb[nxt][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks + 1]);
+                    } else {
+                        const int i = q == 1 ? 0 : q - 2;
+                        fa[nxt][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks + 1]);
+                    }
+                }
+            };
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 acc[m >> 1][m & 1] =
                     __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m >> 1], fb[cur][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
+                read_next(m);
+                if (m == M - 1) {
+#pragma unroll
+                    for (int q = M; q < NA + 2; ++q) read_next(q);
+                }
                 if (ks < SPREAD) {
                     // after MFMA m the number of issued loads is topped up to ceil((m+1) Q / M)
                     const int lo = (m * Q + M - 1) / M, hi = ((m + 1) * Q + M - 1) / M;
 #pragma unroll
                     for (int t = lo; t < hi; ++t) dma(ks * Q + t);
                 }
+                __builtin_amdgcn_sched_barrier(0);      // keep this interleaving
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     } else {
 #pragma unroll
@@ -168,6 +187,13 @@ __device__ __forceinline__ void dma16_to_lds(const void* gptr, uint32_t lds_base
                  : "v"(gptr), "s"(lds_base)
                  : "memory", "m0");
 }
+// Same, 4 bytes per lane: lane l lands at lds_base + 4 l.
+__device__ __forceinline__ void dma4_to_lds(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));   // LDS aperture: low 32 bits are the offset
 }
@@ -178,7 +204,8 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <bool LONG, int G, bool ARG, int BK, int NS, bool DMA, int SPREAD = BK / 32>
+
+template <bool ARG, int BK, int NS, bool DMA, int SPREAD = BK / 32>
 __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     static_assert(BK == 64 || BK == 32, "slab depth");
     static_assert(DMA || (BK == 64 && NS == 2), "register-staged loader is BK = 64, two stages");
@@ -205,10 +232,14 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
         else if constexpr (ST == 2) return &s_ring2[0][0];
         else return &s_ring3[0][0];
     };
-    __shared__ int s_rowtok[FWD_TM];     // row of H (b*S+s) feeding each tile row
-    __shared__ int s_rowpos[FWD_TM];     // sequence position s of each tile row
-    __shared__ float s_xm[4][2][32];
-    __shared__ int s_xs[4][2][32];
+    // Row tables of the current and the next tile (double buffered: the next tile's are fetched,
+    // straight into LDS, while this one is multiplied).
+    __shared__ __attribute__((aligned(1024))) int2 s_rows[2][FWD_TM];   // (row of H = b*S+s, position s) per tile row
+    // blk_meta of each tile block, indexed t % 4: the scan of tile t-1 may still be reading its records
+    // when the records of tile t+1 arrive
+    __shared__ __attribute__((aligned(64))) int s_meta[4][16];
+    __shared__ float s_pm[FWD_TB][FWD_TN];   // per (block, column): max logit of the block
+    __shared__ int s_ps[FWD_TB][FWD_TN];     //                      and its position
 
     // ---- workgroup -> (row group, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
@@ -221,6 +252,10 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     const int vt = vg * FWD_GV + (rem - rg * FWD_GV);
     if (vt >= p.n_vtiles) return;
     const int v0 = vt * FWD_TN;
+    const int gb_lo = p.grp_blk0[rg];
+    const int nb = p.grp_blk0[rg + 1] - gb_lo;     // blocks of this row group
+    if (nb <= 0) return;
+    const int n_tiles = (nb + FWD_TB - 1) / FWD_TB;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -246,63 +281,50 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
         wptr[j] = p.W + (size_t)v * D + gch * 8;
     }
     // ---- fragment geometry ----
-    // Row blocks of a wave: the long layout interleaves them between the two waves that share a SIMD
-    // (wave wm owns tile row blocks wm, wm+2, wm+4, wm+6) so that a short last chunk splits evenly;
-    // the short layout keeps them contiguous (4 wm .. 4 wm + 3): a sequence slot must not straddle waves.
-    const int fa_row = (LONG ? wm * 32 : wm * 128) + l32;
-    constexpr int A_STRIDE = (LONG ? 64 : 32) * RB;           // bytes between a wave's consecutive row blocks
+    // Tile blocks are interleaved between the two waves that share a SIMD (wave wm owns tile blocks
+    // wm, wm+2, wm+4, wm+6), so that a short last tile splits evenly between them.
+    const int fa_row = wm * FWD_BLK + l32;
+    constexpr int A_STRIDE = 2 * FWD_BLK * RB;                // bytes between a wave's consecutive row blocks
     constexpr int B_STRIDE = 32 * RB;
     const int fb_row = wn * 64 + l32;
     int fsw[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fsw[ks] = ((ks * 2 + half) ^ lds_swz<BK>(l32)) << 4;
 
-    int len_b = 0, b_long = 0, n_chunks = 1;
-    if (LONG) {
-        b_long = rg;
-        len_b = p.len[b_long];
-        if (len_b == 0) {                            // no valid token: Y = 0, I = 0
-            if (tid < FWD_TN && v0 + tid < p.V) {
-                p.Y[(size_t)b_long * p.V + v0 + tid] = 0.f;
-                if (ARG) p.I[(size_t)b_long * p.V + v0 + tid] = 0;
-            }
-            return;
+    // ---- row tables of tile t into buffer buf, by direct-to-LDS loads (no registers held while the
+    //      tile before it is multiplied): waves 0 and 1 bring 128 rows each (two per lane), wave 2
+    //      the block records.  Rows of dead blocks of a short last tile repeat its last live rows. ----
+    auto fetch_rows = [&](int t, int buf) {
+        const int nact_t = min(FWD_TB, nb - FWD_TB * t);
+        const size_t b0 = (size_t)gb_lo + (size_t)FWD_TB * t;
+        if (wave < 2) {
+            const int r = min(2 * (wave * 64 + lane), nact_t * FWD_BLK - 2);
+            dma16_to_lds(p.rows + b0 * FWD_BLK + r,
+                         __builtin_amdgcn_readfirstlane(lds_addr(&s_rows[buf][0]) + wave * 1024));
+        } else if (wave == 2 && lane < nact_t) {
+            dma4_to_lds(p.blk_meta + b0 + lane, __builtin_amdgcn_readfirstlane(lds_addr(&s_meta[t & 3][0])));
         }
-        n_chunks = (len_b + FWD_TM - 1) / FWD_TM;
-    }
+    };
+    fetch_rows(0, 0);
+    wait_vmcnt<0>();
 
-    float run_m[2] = {-INFINITY, -INFINITY};
-    int run_s[2] = {0, 0};
+    // scan state of thread tid < 256 (column v0 + tid): running pair of the sequence still open
+    float run_m = -INFINITY;
+    int run_s = 0;
+    const int v_out = v0 + tid;
+    const float bias_v = (tid < FWD_TN && v_out < p.V) ? p.bias[v_out] : 0.f;
+    __syncthreads();
 
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        // Row blocks (of 32 rows) that hold real tokens in this chunk; na = how many of them belong
-        // to this wave.  The others are not multiplied.
-        int na = 4;
-        if (LONG) {
-            const int rows = min(FWD_TM, len_b - chunk * FWD_TM);
-            na = (((rows + 31) >> 5) + 1 - wm) >> 1;
-        }
-        // ---- which token feeds each tile row ----
-        if (tid < FWD_TM) {
-            int b, j, lb;
-            if (LONG) {
-                b = b_long; lb = len_b; j = chunk * FWD_TM + tid;
-            } else {
-                constexpr int SR = 32 * G;
-                b = rg * (FWD_TM / SR) + tid / SR;
-                b = b < p.B ? b : p.B - 1;
-                lb = p.len[b];
-                j = tid % SR;
-            }
-            j = j < lb ? j : lb - 1;
-            const int s = lb > 0 ? p.pos[(size_t)b * p.S + j] : 0;
-            s_rowtok[tid] = b * p.S + s;
-            s_rowpos[tid] = s;
-        }
-        __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
+        const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
+        const bool has_next = t + 1 < n_tiles;
         const uint16_t* hptr[IPW];
 #pragma unroll
-        for (int j = 0; j < IPW; ++j) hptr[j] = p.H + (size_t)s_rowtok[lrow + 8 * RPI * j] * D + gch * 8;
+        for (int j = 0; j < IPW; ++j) hptr[j] = p.H + (size_t)s_rows[buf][lrow + 8 * RPI * j].x * D + gch * 8;
+        // next tile's tables: in flight with the first slab, published by the slab loop's barriers
+        if (has_next) fetch_rows(t + 1, buf ^ 1);
 
         floatx16 acc[4][2];
 #pragma unroll
@@ -327,7 +349,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 for (int n = 0; n < LPT; ++n) issue_one(st, kt, n);
             };
             // The whole slab loop is instantiated once per count NA of live row blocks and the choice is
-            // made per chunk, outside the loop, so that each instance is straight-line MFMA code.
+            // made per tile, outside the loop, so that each instance is straight-line MFMA code.
             auto run_slabs = [&](auto na_c) {
                 constexpr int NA = decltype(na_c)::value;
                 // One pipeline step for slab kt, which lives in stage ST (compile-time so that every
@@ -413,96 +435,64 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
             }
         }
 
-        // ---- epilogue: in-lane max/argmax over each slot's rows ----
-        constexpr int NSLOT = 4 / G;
+        // ---- epilogue, part 1: every live block of this wave -> one (max, position) per column ----
 #pragma unroll
-        for (int q = 0; q < NSLOT; ++q) {
-            float m[2];
-            int e[2];
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                m[c] = -INFINITY;
-                e[c] = 0;
-#pragma unroll
-                for (int i = q * G; i < q * G + G; ++i) {
-                    if (i < na) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const float a = acc[i][c][r];
-                            if (ARG) {
-                                if (a > m[c]) { m[c] = a; e[c] = i * 16 + r; }
-                            } else {
-                                m[c] = fmaxf(m[c], a);
-                            }
-                        }
-                    }
-                }
-            }
-            if (LONG) {
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const int s = ARG ? s_rowpos[acc_row<LONG>(e[c], half, wm)] : 0;
-                    if (m[c] > run_m[c]) { run_m[c] = m[c]; run_s[c] = s; }
-                }
-            } else {
-                // a slot lives entirely in this wave: combine the two half-waves and write
+        for (int i = 0; i < 4; ++i) {
+            if (i < na) {
+                const int blk = 2 * i + wm;
                 float mm[2];
                 int ss[2];
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    int s = ARG ? s_rowpos[acc_row<LONG>(e[c], half, wm)] : 0;
-                    const float mo = __shfl_xor(m[c], 32);
+                    // rows grow with the register index, and positions with the rows: the first
+                    // register that holds the maximum is the lowest position in this lane
+                    float m = acc[i][c][0];
+                    int e = 0;
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) {
+                        const float a = acc[i][c][r];
+                        if (ARG) {
+                            if (a > m) { m = a; e = r; }
+                        } else {
+                            m = fmaxf(m, a);
+                        }
+                    }
+                    int s = ARG ? s_rows[buf][acc_row(blk, e, half)].y : 0;
+                    const float mo = __shfl_xor(m, 32);
                     const int so = __shfl_xor(s, 32);
-                    float mc = m[c];
-                    if (mo > mc || (mo == mc && so < s)) { mc = mo; s = so; }
-                    mm[c] = mc;
+                    if (mo > m || (mo == m && so < s)) { m = mo; s = so; }
+                    mm[c] = m;
                     ss[c] = s;
                 }
-                constexpr int SPT = FWD_TM / (32 * G);            // sequences per tile
-                const int b = rg * SPT + wm * NSLOT + q;
-                const int v = v0 + wn * 64 + half * 32 + l32;
-                if (b < p.B && v < p.V) {
-                    const float mv = half ? mm[1] : mm[0];
-                    const int sv = half ? ss[1] : ss[0];
-                    const bool any = p.len[b] > 0;
-                    const float y = any ? log1pf(fmaxf(mv + p.bias[v], 0.f)) : 0.f;
-                    p.Y[(size_t)b * p.V + v] = y;
-                    if (ARG) p.I[(size_t)b * p.V + v] = any ? sv : 0;
-                }
+                // both half-waves now hold both columns; half h stores column 32 h + l32
+                const int col = wn * 64 + half * 32 + l32;
+                s_pm[blk][col] = half ? mm[1] : mm[0];
+                if (ARG) s_ps[blk][col] = half ? ss[1] : ss[0];
             }
         }
-        __syncthreads();     // the next chunk rewrites the row tables and the ring
-    }
-
-    if (LONG) {
-        // combine half-waves, then the two waves that share these columns, then finalise
-        float mm[2];
-        int ss[2];
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            float mc = run_m[c];
-            int s = run_s[c];
-            const float mo = __shfl_xor(mc, 32);
-            const int so = __shfl_xor(s, 32);
-            if (mo > mc || (mo == mc && so < s)) { mc = mo; s = so; }
-            mm[c] = mc;
-            ss[c] = s;
-        }
-        if (wm == 1 && half == 0) {
-#pragma unroll
-            for (int c = 0; c < 2; ++c) { s_xm[wn][c][l32] = mm[c]; s_xs[wn][c][l32] = ss[c]; }
-        }
+        wait_vmcnt<0>();     // (the next tile's tables, if the slab loop was too short to wait for them)
         __syncthreads();
-        if (wm == 0) {
-            float mv = half ? mm[1] : mm[0];
-            int sv = half ? ss[1] : ss[0];
-            const float mo = s_xm[wn][half][l32];
-            const int so = s_xs[wn][half][l32];
-            if (mo > mv || (mo == mv && so < sv)) { mv = mo; sv = so; }
-            const int v = v0 + wn * 64 + half * 32 + l32;
-            if (v < p.V) {
-                p.Y[(size_t)b_long * p.V + v] = log1pf(fmaxf(mv + p.bias[v], 0.f));
-                if (ARG) p.I[(size_t)b_long * p.V + v] = sv;
+        // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
+        //      the first four waves take part, the others go on to the next tile. ----
+        if (tid < FWD_TN) {
+            for (int k = 0; k < nact; ++k) {
+                const float m = s_pm[k][tid];
+                if (m > run_m) {                  // later blocks hold higher positions: strict
+                    run_m = m;
+                    if (ARG) run_s = s_ps[k][tid];
+                }
+                const int meta = s_meta[t & 3][k];
+                if (meta & FWD_META_LAST) {
+                    if (v_out < p.V) {
+                        const int b = meta & (FWD_META_EMPTY - 1);
+                        const bool any = !(meta & FWD_META_EMPTY);
+                        const size_t o = (size_t)b * p.V + v_out;
+                        p.Y[o] = any ? log1pf(fmaxf(run_m + bias_v, 0.f)) : 0.f;
+                        if (ARG) p.I[o] = any ? run_s : 0;
+                    }
+                    run_m = -INFINITY;
+                    run_s = 0;
+                }
             }
         }
     }

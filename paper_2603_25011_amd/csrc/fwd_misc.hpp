@@ -42,6 +42,79 @@ __global__ __launch_bounds__(PREP_THREADS) void fwd_prep_kernel(const uint8_t* _
     if (tid == 0) len[b] = base;
 }
 
+// Packing plan for the MFMA forward.  Every sequence takes ceil(len / 32) blocks of 32 rows (one
+// block if it has no valid token, so that its zero output is still written); blk0 is the exclusive
+// prefix sum of the block counts, and the block list is cut into n_groups contiguous ranges of whole
+// sequences with about equal block counts: group g starts at the first sequence whose first block
+// is not below g * total / n_groups.  One workgroup; B and n_groups are small next to the GEMM.
+constexpr int PLAN_THREADS = 256;
+
+__global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __restrict__ len, int* blk0,
+                                                                 int* __restrict__ grp_blk0, int B,
+                                                                 int n_groups) {
+    __shared__ int s_scan[PLAN_THREADS];
+    const int tid = threadIdx.x;
+    int base = 0;
+    for (int b0 = 0; b0 < B; b0 += PLAN_THREADS) {
+        const int b = b0 + tid;
+        int n = 0;
+        if (b < B) {
+            n = (len[b] + 31) >> 5;
+            n = n > 0 ? n : 1;
+        }
+        s_scan[tid] = n;
+        __syncthreads();
+        for (int off = 1; off < PLAN_THREADS; off <<= 1) {
+            const int add = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += add;
+            __syncthreads();
+        }
+        if (b < B) blk0[b] = base + s_scan[tid] - n;
+        base += s_scan[PLAN_THREADS - 1];
+        __syncthreads();
+    }
+    if (tid == 0) blk0[B] = base;
+    // the prefix sums are read back below by other threads of this workgroup: make them visible at
+    // device scope and read them with device-scope loads (no stale line of the vector L1)
+    __threadfence();
+    __syncthreads();
+    const int total = base;
+    for (int g = tid; g <= n_groups; g += PLAN_THREADS) {
+        const int target = (int)(((long long)g * total) / n_groups);
+        int lo = 0, hi = B;                       // smallest b in [0, B] with blk0[b] >= target
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            const int x = __hip_atomic_load(&blk0[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (x >= target) hi = mid; else lo = mid + 1;
+        }
+        grp_blk0[g] = g == n_groups ? total : __hip_atomic_load(&blk0[lo], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Row table of the packed layout, one workgroup per sequence: packed row k of the sequence reads
+// token pos[min(k, len-1)] (the tail of the last block repeats the last valid token), and every
+// block records its sequence, whether it ends it, and whether the sequence is empty.
+constexpr int FWD_ROWS_THREADS = 256;
+
+__global__ __launch_bounds__(FWD_ROWS_THREADS) void fwd_rows_kernel(const int* __restrict__ len,
+                                                                     const int* __restrict__ pos,
+                                                                     const int* __restrict__ blk0,
+                                                                     int2* __restrict__ rows,
+                                                                     int* __restrict__ blk_meta, int S) {
+    const int b = blockIdx.x;
+    const int n = len[b];
+    const int g0 = blk0[b];
+    const int nblk = blk0[b + 1] - g0;
+    const int* prow = pos + (size_t)b * S;
+    for (int k = threadIdx.x; k < nblk * 32; k += FWD_ROWS_THREADS) {
+        const int s = n > 0 ? prow[k < n ? k : n - 1] : 0;
+        rows[(size_t)g0 * 32 + k] = make_int2(b * S + s, s);
+    }
+    for (int k = threadIdx.x; k < nblk; k += FWD_ROWS_THREADS)
+        blk_meta[g0 + k] = b | (k == nblk - 1 ? (1 << 31) : 0) | (n == 0 ? (1 << 30) : 0);
+}
+
 // Plain fp32 head: one thread per (b, v), looping over valid positions and the hidden size with
 // fp32 FMAs.  Eq. 1 evaluated with the max taken before the activation (Sec. 3).  Not tuned: it
 // exists so that small fp32 problems run through the same entry points.

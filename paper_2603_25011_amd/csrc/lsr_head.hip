@@ -35,14 +35,37 @@ int check_desc(const lsr_head_desc* d, Shape* out) {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// ---- forward workspace: len[B] | pos[B*S] ----
-struct FwdWs { size_t len_off, pos_off, total; };
+// ---- forward workspace: len[B] | pos[B*S] | blk0[B+1] | grp_blk0[groups+1] | blk_meta[blocks] |
+//      rows[blocks*32], blocks = B * ceil(S/32) being the most the packed layout can need ----
+constexpr int FWD_MAX_GROUPS = 1024;
+struct FwdWs { size_t len_off, pos_off, blk0_off, grp_off, meta_off, rows_off, total; };
 FwdWs fwd_ws(const Shape& s) {
     FwdWs w;
+    const size_t blocks = (size_t)s.B * ((s.S + 31) / 32);
     w.len_off = 0;
     w.pos_off = w.len_off + align_up(sizeof(int) * (size_t)s.B);
-    w.total = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
+    w.blk0_off = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
+    w.grp_off = w.blk0_off + align_up(sizeof(int) * ((size_t)s.B + 1));
+    w.meta_off = w.grp_off + align_up(sizeof(int) * (FWD_MAX_GROUPS + 1));
+    w.rows_off = w.meta_off + align_up(sizeof(int) * blocks);
+    w.total = w.rows_off + align_up(sizeof(int2) * blocks * 32);
     return w;
+}
+
+// Row groups of the packed forward: about four tiles (32 blocks) per group, which measured best
+// over the shipped workloads (many groups: more workgroups to balance; few groups: fewer short last
+// tiles and more reuse of a vocabulary tile).  Lengths are not known on the host, so the block count
+// is an estimate: sequences are taken to fill 70 % of S, and every sequence has at least one block.
+int fwd_row_groups(const Shape& s) {
+    const long per_seq_max = (s.S + 31) / 32;
+    long per_seq10 = per_seq_max * 7;                    // tenths of a block
+    if (per_seq10 < 10) per_seq10 = 10;
+    const long blocks = (long)s.B * per_seq10 / 10;
+    long ng = (blocks + 16) / 32;
+    if (ng > s.B) ng = s.B;
+    if (ng > FWD_MAX_GROUPS) ng = FWD_MAX_GROUPS;
+    if (ng < 1) ng = 1;
+    return (int)ng;
 }
 
 // ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] ----
@@ -118,15 +141,14 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : L
 
 // Loader choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab, else the
 // register-staged loader that can zero-fill the last slab.
-template <bool LONG, int G>
 void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
     const dim3 grid((p.n_logical + 7) / 8 * 8), block(FWD_THREADS);
     if (p.D % 64 == 0) {
-        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, true>), grid, block, 0, st, p);
-        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, true>), grid, block, 0, st, p);
+        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, 64, 2, true>), grid, block, 0, st, p);
+        else     hipLaunchKernelGGL((fwd_bf16_kernel<false, 64, 2, true>), grid, block, 0, st, p);
     } else {
-        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, true, 64, 2, false>), grid, block, 0, st, p);
-        else     hipLaunchKernelGGL((fwd_bf16_kernel<LONG, G, false, 64, 2, false>), grid, block, 0, st, p);
+        if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, 64, 2, false>), grid, block, 0, st, p);
+        else     hipLaunchKernelGGL((fwd_bf16_kernel<false, 64, 2, false>), grid, block, 0, st, p);
     }
 }
 
@@ -152,6 +174,17 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
 
     prof.begin(0);
     hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
+    char* base = static_cast<char*>(ws);
+    int* blk0 = reinterpret_cast<int*>(base + w.blk0_off);
+    int* grp_blk0 = reinterpret_cast<int*>(base + w.grp_off);
+    int* blk_meta = reinterpret_cast<int*>(base + w.meta_off);
+    int2* rows = reinterpret_cast<int2*>(base + w.rows_off);
+    const int n_vtiles = (s.V + FWD_TN - 1) / FWD_TN;
+    const int n_rowgroups = fwd_row_groups(s);
+    if (s.dtype == LSR_BF16) {
+        hipLaunchKernelGGL(fwd_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, len, blk0, grp_blk0, s.B, n_rowgroups);
+        hipLaunchKernelGGL(fwd_rows_kernel, dim3(s.B), dim3(FWD_ROWS_THREADS), 0, st, len, pos, blk0, rows, blk_meta, s.S);
+    }
     prof.end(0);
     if ((rc = launch_status()) != LSR_OK) return rc;
 
@@ -166,23 +199,13 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         FwdParams p;
         p.H = static_cast<const uint16_t*>(H);
         p.W = static_cast<const uint16_t*>(W);
-        p.bias = bias; p.len = len; p.pos = pos; p.Y = Y; p.I = I;
+        p.bias = bias; p.rows = rows; p.blk_meta = blk_meta; p.grp_blk0 = grp_blk0; p.Y = Y; p.I = I;
         p.B = s.B; p.S = s.S; p.D = s.D; p.V = s.V;
-        p.n_vtiles = (s.V + FWD_TN - 1) / FWD_TN;
+        p.n_vtiles = n_vtiles;
         const int n_vgroups = (p.n_vtiles + FWD_GV - 1) / FWD_GV;
-        if (s.S > 128) {
-            p.n_rowgroups = s.B;
-            p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            launch_fwd_bf16<true, 4>(p, I != nullptr, st);
-        } else {
-            const int G = s.S <= 32 ? 1 : (s.S <= 64 ? 2 : 4);
-            const int spt = FWD_TM / (32 * G);
-            p.n_rowgroups = (s.B + spt - 1) / spt;
-            p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
-            if (G == 1) launch_fwd_bf16<false, 1>(p, I != nullptr, st);
-            else if (G == 2) launch_fwd_bf16<false, 2>(p, I != nullptr, st);
-            else launch_fwd_bf16<false, 4>(p, I != nullptr, st);
-        }
+        p.n_rowgroups = n_rowgroups;
+        p.n_logical = n_vgroups * FWD_GV * p.n_rowgroups;
+        launch_fwd_bf16(p, I != nullptr, st);
     }
     prof.end(1);
     return launch_status();

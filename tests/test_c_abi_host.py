@@ -46,7 +46,7 @@ def test_workspace_sizes_scale_as_documented(lib):
     # forward: O(B*S); backward: O(B*V); nothing proportional to B*S*V
     fw = f(64, 512, 1024, 250002, lsr.LSR_BF16, False)
     bw = f(64, 512, 1024, 250002, lsr.LSR_BF16, True)
-    assert 4 * 64 * 512 <= fw <= 8 * 64 * 512 + 4096
+    assert 4 * 64 * 512 <= fw <= 16 * 64 * 512 + 16384
     assert 8 * 64 * 250002 <= bw <= 16 * 64 * 250002
     assert bw < 64 * 512 * 250002 // 8
     # long sequences do not blow up the backward count table
