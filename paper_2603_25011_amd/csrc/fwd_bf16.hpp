@@ -46,12 +46,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int FWD_TM = 256;        // tile rows (tokens)
-constexpr int FWD_TN = 256;        // tile columns (vocabulary entries)
-constexpr int FWD_THREADS = 512;
-#ifndef LSR_FWD_GV
-#define LSR_FWD_GV 4
-#endif
-constexpr int FWD_GV = LSR_FWD_GV;   // vocabulary tiles per L2-sharing group
+// A workgroup has 2 x NWN waves: two wave rows (wm) that split the tile's row blocks, NWN wave
+// columns (wn) of 64 vocabulary entries each.
+constexpr int fwd_tn(int nwn) { return 64 * nwn; }          // tile columns (vocabulary entries)
+constexpr int fwd_threads(int nwn) { return 128 * nwn; }
+constexpr int FWD_GV_COLS = 1024;  // vocabulary entries per L2-sharing group of tiles
 
 constexpr int FWD_BLK = 32;                      // rows per block
 constexpr int FWD_TB = FWD_TM / FWD_BLK;         // blocks per tile
@@ -68,9 +67,10 @@ struct FwdParams {
     float* Y;
     int* I;                  // may be null
     int B, S, D, V;
-    int n_vtiles;            // ceil(V / 256)
+    int n_vtiles;            // ceil(V / tile columns)
     int n_rowgroups;
-    int n_logical;           // ceil(n_vtiles / GV) * GV * n_rowgroups
+    int gv;                  // vocabulary tiles per L2-sharing group
+    int n_logical;           // ceil(n_vtiles / gv) * gv * n_rowgroups
 };
 
 // Swizzle of the 16-byte chunk index inside a tile row.  A fragment read has lanes 0..31 on 32
@@ -205,32 +205,45 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 
-template <bool ARG, int BK, int NS, bool DMA, int SPREAD = BK / 32>
-__global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
+// NWN   wave columns (4: 8 waves, 256 x 256 tile, one workgroup per CU;
+//                     2: 4 waves, 256 x 128 tile, two workgroups per CU that hide each other's
+//                        barriers, load waits and epilogues)
+// PMRING  the per-block maxima of the epilogue live in a ring stage that is idle by then instead of
+//         in LDS of their own (needed to fit two workgroups of three stages in 160 KB)
+template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int SPREAD = BK / 32>
+__global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams p) {
     static_assert(BK == 64 || BK == 32, "slab depth");
-    static_assert(DMA || (BK == 64 && NS == 2), "register-staged loader is BK = 64, two stages");
+    static_assert(DMA || (BK == 64 && NS == 2 && NWN == 4), "register-staged loader: BK = 64, two stages, 8 waves");
+    static_assert(!PMRING || (DMA && NS == 3), "epilogue maxima borrow the idle third stage");
+    constexpr int NW = 2 * NWN;              // waves
+    constexpr int TN = fwd_tn(NWN);
     constexpr int RB = BK * 2;               // bytes per tile row per slab
     constexpr int CPR = RB / 16;             // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;            // rows covered by one wave-wide 16-byte-per-lane access
-    constexpr int IPW = FWD_TM / RPI / 8;    // such accesses per wave, operand and slab
+    constexpr int IPA = FWD_TM / RPI / NW;   // such accesses per wave and slab, token rows
+    constexpr int IPB = TN / RPI / NW;       //                                  vocabulary rows
     constexpr int KS = BK / 16;              // MFMA k-steps per slab
-    constexpr int SLAB = FWD_TM * RB;        // bytes per operand per stage
-    constexpr int LPT = 2 * IPW;             // loads per thread per slab (A then B)
+    constexpr int SLAB_A = FWD_TM * RB;      // bytes per stage, token operand
+    constexpr int SLAB_B = TN * RB;          //                  vocabulary operand
+    constexpr int STAGE = SLAB_A + SLAB_B;
+    constexpr int LPT = IPA + IPB;           // loads per thread per slab (A then B)
+    constexpr int JSTEP = NW * 1024;         // LDS bytes between a wave's consecutive accesses
+    constexpr int PM_BYTES = FWD_TB * TN * 4;
+    static_assert(!PMRING || 2 * PM_BYTES <= STAGE, "maxima and positions must fit one stage");
 
-    // One array per ring stage ([A|B][SLAB] each): distinct objects let the compiler see that a
-    // fragment read of one stage cannot alias a direct-to-LDS load into another, so it does not
-    // serialise them with a full vmcnt wait.  Stages beyond NS are never referenced and cost nothing.
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring0[2][SLAB];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring1[2][SLAB];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring2[2][SLAB];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring3[2][SLAB];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_pair[2][2][SLAB];    // register-staged loader only
+    // One array per ring stage: distinct objects keep the compiler from serialising a fragment read
+    // of one stage against traffic into another.  Stages beyond NS are never referenced and cost nothing.
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring0[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring1[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring2[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_ring3[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t s_pair[2][STAGE];      // register-staged loader only
     auto ring = [&](auto st) -> uint8_t* {
         constexpr int ST = decltype(st)::value;
-        if constexpr (ST == 0) return &s_ring0[0][0];
-        else if constexpr (ST == 1) return &s_ring1[0][0];
-        else if constexpr (ST == 2) return &s_ring2[0][0];
-        else return &s_ring3[0][0];
+        if constexpr (ST == 0) return &s_ring0[0];
+        else if constexpr (ST == 1) return &s_ring1[0];
+        else if constexpr (ST == 2) return &s_ring2[0];
+        else return &s_ring3[0];
     };
     // Row tables of the current and the next tile (double buffered: the next tile's are fetched,
     // straight into LDS, while this one is multiplied).
@@ -238,20 +251,20 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     // blk_meta of each tile block, indexed t % 4: the scan of tile t-1 may still be reading its records
     // when the records of tile t+1 arrive
     __shared__ __attribute__((aligned(64))) int s_meta[4][16];
-    __shared__ float s_pm[FWD_TB][FWD_TN];   // per (block, column): max logit of the block
-    __shared__ int s_ps[FWD_TB][FWD_TN];     //                      and its position
+    // per (block, column): max logit of the block and its position
+    __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[PMRING ? 16 : 2 * PM_BYTES];
 
     // ---- workgroup -> (row group, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= p.n_logical) return;
-    const int group_span = p.n_rowgroups * FWD_GV;
+    const int group_span = p.n_rowgroups * p.gv;
     const int vg = logical / group_span;
     const int rem = logical - vg * group_span;
-    const int rg = rem / FWD_GV;
-    const int vt = vg * FWD_GV + (rem - rg * FWD_GV);
+    const int rg = rem / p.gv;
+    const int vt = vg * p.gv + (rem - rg * p.gv);
     if (vt >= p.n_vtiles) return;
-    const int v0 = vt * FWD_TN;
+    const int v0 = vt * TN;
     const int gb_lo = p.grp_blk0[rg];
     const int nb = p.grp_blk0[rg + 1] - gb_lo;     // blocks of this row group
     if (nb <= 0) return;
@@ -260,28 +273,28 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave >> 2;
-    const int wn = wave & 3;
+    const int wm = wave / NWN;
+    const int wn = wave % NWN;
     const int half = lane >> 5;
     const int l32 = lane & 31;
     const int D = p.D;
     const int nk = (D + BK - 1) / BK;
 
-    // ---- loader geometry: access j of wave w covers tile rows (8 j + w) RPI .. + RPI, 1024 contiguous
+    // ---- loader geometry: access j of wave w covers tile rows (NW j + w) RPI .. + RPI, 1024 contiguous
     //      LDS bytes; lane -> (row lrow, LDS chunk slot lp), which holds global chunk lp ^ swizzle(row) ----
-    const int lrow = wave * RPI + lane / CPR;                 // + 8 RPI j
+    const int lrow = wave * RPI + lane / CPR;                 // + NW RPI j
     const int lp = lane % CPR;
     const int gch = lp ^ lds_swz<BK>(lrow);                   // swizzle bits do not depend on j
-    const int st_off = lrow * RB + lp * 16;                   // + 8192 j   (register-staged loader)
-    const uint16_t* wptr[IPW];
+    const int st_off = lrow * RB + lp * 16;                   // + JSTEP j   (register-staged loader)
+    const uint16_t* wptr[IPB];
 #pragma unroll
-    for (int j = 0; j < IPW; ++j) {
-        int v = v0 + lrow + 8 * RPI * j;
+    for (int j = 0; j < IPB; ++j) {
+        int v = v0 + lrow + NW * RPI * j;
         v = v < p.V ? v : p.V - 1;
         wptr[j] = p.W + (size_t)v * D + gch * 8;
     }
     // ---- fragment geometry ----
-    // Tile blocks are interleaved between the two waves that share a SIMD (wave wm owns tile blocks
+    // Tile blocks are interleaved between the two wave rows (wave row wm owns tile blocks
     // wm, wm+2, wm+4, wm+6), so that a short last tile splits evenly between them.
     const int fa_row = wm * FWD_BLK + l32;
     constexpr int A_STRIDE = 2 * FWD_BLK * RB;                // bytes between a wave's consecutive row blocks
@@ -308,11 +321,11 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
     fetch_rows(0, 0);
     wait_vmcnt<0>();
 
-    // scan state of thread tid < 256 (column v0 + tid): running pair of the sequence still open
+    // scan state of thread tid < TN (column v0 + tid): running pair of the sequence still open
     float run_m = -INFINITY;
     int run_s = 0;
     const int v_out = v0 + tid;
-    const float bias_v = (tid < FWD_TN && v_out < p.V) ? p.bias[v_out] : 0.f;
+    const float bias_v = (tid < TN && v_out < p.V) ? p.bias[v_out] : 0.f;
     __syncthreads();
 
     for (int t = 0; t < n_tiles; ++t) {
@@ -320,9 +333,9 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
         const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
         const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
         const bool has_next = t + 1 < n_tiles;
-        const uint16_t* hptr[IPW];
+        const uint16_t* hptr[IPA];
 #pragma unroll
-        for (int j = 0; j < IPW; ++j) hptr[j] = p.H + (size_t)s_rows[buf][lrow + 8 * RPI * j].x * D + gch * 8;
+        for (int j = 0; j < IPA; ++j) hptr[j] = p.H + (size_t)s_rows[buf][lrow + NW * RPI * j].x * D + gch * 8;
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(t + 1, buf ^ 1);
 
@@ -341,8 +354,8 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
             auto issue_one = [&](auto st, int kt, int n) {
                 const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr(ring(st)) + wave * 1024);
                 const int koff = kt * BK;
-                if (n < IPW) dma16_to_lds(hptr[n] + koff, dst + n * 8192);
-                else dma16_to_lds(wptr[n - IPW] + koff, dst + SLAB + (n - IPW) * 8192);
+                if (n < IPA) dma16_to_lds(hptr[n] + koff, dst + n * JSTEP);
+                else dma16_to_lds(wptr[n - IPA] + koff, dst + SLAB_A + (n - IPA) * JSTEP);
             };
             auto issue = [&](auto st, int kt) {
 #pragma unroll
@@ -372,7 +385,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                         for (int n = 0; n < LPT; ++n) dma(n);
                     } else {
                         const uint8_t* sa = ring(st) + fa_row * RB;
-                        const uint8_t* sb = ring(st) + SLAB + fb_row * RB;
+                        const uint8_t* sb = ring(st) + SLAB_A + fb_row * RB;
                         mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
                     }
                 };
@@ -394,32 +407,31 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 default: run_slabs(std::integral_constant<int, 0>{}); break;
             }
         } else {
-            uint4 ra[IPW], rb[IPW];
+            uint4 ra[IPA], rb[IPB];
             // K slabs are full except possibly the last one (D not a multiple of 64): only that one
             // pays for per-chunk predication.
             auto gload = [&](int kt) {
                 const int koff = kt * BK;
                 if (koff + BK <= D) {
 #pragma unroll
-                    for (int j = 0; j < IPW; ++j) {
-                        ra[j] = *reinterpret_cast<const uint4*>(hptr[j] + koff);
-                        rb[j] = *reinterpret_cast<const uint4*>(wptr[j] + koff);
-                    }
+                    for (int j = 0; j < IPA; ++j) ra[j] = *reinterpret_cast<const uint4*>(hptr[j] + koff);
+#pragma unroll
+                    for (int j = 0; j < IPB; ++j) rb[j] = *reinterpret_cast<const uint4*>(wptr[j] + koff);
                 } else {
                     const bool kval = koff + gch * 8 < D;
 #pragma unroll
-                    for (int j = 0; j < IPW; ++j) {
+                    for (int j = 0; j < IPA; ++j)
                         ra[j] = kval ? *reinterpret_cast<const uint4*>(hptr[j] + koff) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < IPB; ++j)
                         rb[j] = kval ? *reinterpret_cast<const uint4*>(wptr[j] + koff) : make_uint4(0, 0, 0, 0);
-                    }
                 }
             };
             auto lstore = [&](int st) {
 #pragma unroll
-                for (int j = 0; j < IPW; ++j) {
-                    *reinterpret_cast<uint4*>(&s_pair[st][0][st_off + j * 8192]) = ra[j];
-                    *reinterpret_cast<uint4*>(&s_pair[st][1][st_off + j * 8192]) = rb[j];
-                }
+                for (int j = 0; j < IPA; ++j) *reinterpret_cast<uint4*>(&s_pair[st][st_off + j * JSTEP]) = ra[j];
+#pragma unroll
+                for (int j = 0; j < IPB; ++j) *reinterpret_cast<uint4*>(&s_pair[st][SLAB_A + st_off + j * JSTEP]) = rb[j];
             };
             gload(0);
             lstore(0);
@@ -427,8 +439,8 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
             for (int kt = 0; kt < nk; ++kt) {
                 const int st = kt & 1;
                 if (kt + 1 < nk) gload(kt + 1);
-                const uint8_t* sa = &s_pair[st][0][fa_row * RB];
-                const uint8_t* sb = &s_pair[st][1][fb_row * RB];
+                const uint8_t* sa = &s_pair[st][fa_row * RB];
+                const uint8_t* sb = &s_pair[st][SLAB_A + fb_row * RB];
                 mma_dispatch<KS, false, 0, 0>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc, [](int) {});
                 if (kt + 1 < nk) lstore(st ^ 1);
                 __syncthreads();
@@ -436,6 +448,16 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
         }
 
         // ---- epilogue, part 1: every live block of this wave -> one (max, position) per column ----
+        // With PMRING the table borrows the ring stage that slab nk would use: no load was issued
+        // into it after slab nk - NS landed, and nobody reads it during the last slab.
+        float* s_pm;
+        if constexpr (PMRING) {
+            const int idle = nk % NS;
+            s_pm = reinterpret_cast<float*>(idle == 0 ? &s_ring0[0] : (idle == 1 ? &s_ring1[0] : &s_ring2[0]));
+        } else {
+            s_pm = reinterpret_cast<float*>(&s_pm_own[0]);
+        }
+        int* s_ps = reinterpret_cast<int*>(s_pm) + FWD_TB * TN;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (i < na) {
@@ -466,20 +488,20 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 }
                 // both half-waves now hold both columns; half h stores column 32 h + l32
                 const int col = wn * 64 + half * 32 + l32;
-                s_pm[blk][col] = half ? mm[1] : mm[0];
-                if (ARG) s_ps[blk][col] = half ? ss[1] : ss[0];
+                s_pm[blk * TN + col] = half ? mm[1] : mm[0];
+                if (ARG) s_ps[blk * TN + col] = half ? ss[1] : ss[0];
             }
         }
-        wait_vmcnt<0>();     // (the next tile's tables, if the slab loop was too short to wait for them)
+        if (nk < NS) wait_vmcnt<0>();     // the next tile's tables, if the slab loop was too short to wait for them
         __syncthreads();
         // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
-        //      the first four waves take part, the others go on to the next tile. ----
-        if (tid < FWD_TN) {
+        //      the first TN threads take part; without PMRING the others go on to the next tile. ----
+        if (tid < TN) {
             for (int k = 0; k < nact; ++k) {
-                const float m = s_pm[k][tid];
+                const float m = s_pm[k * TN + tid];
                 if (m > run_m) {                  // later blocks hold higher positions: strict
                     run_m = m;
-                    if (ARG) run_s = s_ps[k][tid];
+                    if (ARG) run_s = s_ps[k * TN + tid];
                 }
                 const int meta = s_meta[t & 3][k];
                 if (meta & FWD_META_LAST) {
@@ -495,6 +517,7 @@ __global__ __launch_bounds__(FWD_THREADS) void fwd_bf16_kernel(FwdParams p) {
                 }
             }
         }
+        if constexpr (PMRING) __syncthreads();   // the borrowed stage goes back to the loader
     }
 }
 
