@@ -14,7 +14,10 @@
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller, contiguous row-major,
- *     16-byte aligned.  The library never allocates, frees or keeps device memory.
+ *     16-byte aligned.  The library never allocates, frees or keeps device memory.  Its only
+ *     state is, per device, one auxiliary stream and two events created by the first backward
+ *     call that uses them (small problems run the dW gather beside the dH chain; the work is
+ *     forked from and joined back into `stream`, so the caller sees ordinary stream order).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream)
  *     and the call returns without synchronising, except the *_profiled variants.
  *   - Outputs are overwritten; nothing has to be zeroed by the caller.

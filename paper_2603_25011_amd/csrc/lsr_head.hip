@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "bwd.hpp"
 #include "fwd_bf16.hpp"
 #include "fwd_misc.hpp"
@@ -240,6 +242,40 @@ void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const
     }
 }
 
+// The dW/db gather does not depend on the bucket sort that feeds dH, so the plain (not profiled)
+// backward can run it on an auxiliary stream beside the dH chain: fork after the caller's prior
+// work, join before returning control of the caller's stream.  Measured: the overlap shortens the
+// backward while the gathers are small (B=256 S=32 |V|=30522: 0.42 -> 0.30 ms; B=16 S=256
+// |V|=250002: 1.56 -> 1.47 ms) and lengthens it once they stream tens of GB (B=64 S=512
+// |V|=250002: 7.2 -> 7.7 ms, the two kernels evict each other's L2-resident slices), so it is used
+// up to AUX_MAX_GATHER_BYTES of worst-case gather traffic (2 * B * |V| rows of D elements).  One auxiliary stream and two events per
+// device, created at the first backward on that device and kept until the process ends (default
+// priority, non-blocking with respect to the null stream).
+constexpr double AUX_MAX_GATHER_BYTES = 16e9;
+struct AuxLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ready = false;
+};
+AuxLane* aux_lane() {
+    static AuxLane lanes[64];
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return nullptr; }
+    std::lock_guard<std::mutex> lock(mu);
+    AuxLane& a = lanes[dev];
+    if (!a.ready) {
+        if (hipStreamCreateWithFlags(&a.stream, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        a.ready = true;
+    }
+    return &a;
+}
+
 int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
                   const int32_t* I, float* dH, float* dW, float* db, void* ws, size_t ws_bytes, void* stream,
                   Prof& prof) {
@@ -268,6 +304,20 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     const int n_chunks = s.D / chunk_elems;
     int cpt = 1;
     while (cpt * ROW_THREADS < n_chunks) cpt *= 2;
+
+    // fork: dW/db on the auxiliary stream, the dH chain on the caller's
+    hipStream_t st_main = st;
+    hipStream_t st_dw = st;
+    const double gather_bytes = 2.0 * s.B * s.V * s.D * (s.dtype == LSR_F32 ? 4 : 2);
+    AuxLane* lane = (!prof.on && dH && (dW || db) && gather_bytes <= AUX_MAX_GATHER_BYTES) ? aux_lane() : nullptr;
+    if (lane) {
+        if (hipEventRecord(lane->fork, st_main) != hipSuccess || hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            lane = nullptr;
+        } else {
+            st_dw = lane->stream;
+        }
+    }
 
     if (dH) {
         const dim3 seg_grid(w.n_seg, s.B);
@@ -325,21 +375,27 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
             const int n_groups = (n_dc + NDC - 1) / NDC;
             const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
             if (s.dtype == LSR_F32)
-                hipLaunchKernelGGL((bwd_dw_sliced_kernel<float>), grid, block, lds, st, static_cast<const float*>(H), dY, Y, I,
+                hipLaunchKernelGGL((bwd_dw_sliced_kernel<float>), grid, block, lds, st_dw, static_cast<const float*>(H), dY, Y, I,
                                    dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
             else
-                hipLaunchKernelGGL((bwd_dw_sliced_kernel<uint16_t>), grid, block, lds, st, static_cast<const uint16_t*>(H), dY,
+                hipLaunchKernelGGL((bwd_dw_sliced_kernel<uint16_t>), grid, block, lds, st_dw, static_cast<const uint16_t*>(H), dY,
                                    Y, I, dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
         } else {
             // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows
             VT = VT > 32 ? 32 : VT;
             const size_t lds = (size_t)s.B * VT * 8;
             const dim3 grid((s.V + VT - 1) / VT);
-            if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
-            else launch_dw<uint16_t>(cpt, grid, lds, st, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+            if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st_dw, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+            else launch_dw<uint16_t>(cpt, grid, lds, st_dw, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
         }
         prof.end(4);
         if ((rc = launch_status()) != LSR_OK) return rc;
+    }
+    if (lane) {      // join
+        if (hipEventRecord(lane->join, st_dw) != hipSuccess || hipStreamWaitEvent(st_main, lane->join, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return LSR_ERR_LAUNCH;
+        }
     }
     return LSR_OK;
 }
