@@ -45,17 +45,26 @@ def test_c1_tiny_fp32_forward_backward():
 
 
 @pytest.mark.parametrize("B,S,D,V,len_lo", [
-    (20, 32, 128, 700, 1),      # short layout, 1 row block per sequence, partial last tile, ragged V
-    (7, 48, 64, 300, 5),        # short layout, 2 row blocks per sequence
-    (5, 100, 192, 513, 3),      # short layout, 4 row blocks per sequence
-    (3, 300, 256, 1000, 200),   # long layout, two chunks for some rows
-    (2, 129, 200, 260, 1),      # long layout, K tail (D not a multiple of 64)
+    (20, 32, 128, 700, 1),      # one 32-row block per sequence, short last tile, ragged V
+    (7, 48, 64, 300, 5),        # one or two blocks per sequence
+    (5, 100, 192, 513, 3),      # up to four blocks per sequence
+    (3, 300, 256, 1000, 200),   # sequences that straddle tiles
+    (2, 129, 200, 260, 1),      # K tail (D not a multiple of 64): register-staged loader
     (4, 1, 64, 257, 1),         # S = 1: a plain linear layer
-    (9, 700, 64, 96, 1),        # three chunks, single narrow vocabulary tile
+    (9, 700, 64, 96, 1),        # long sequences, single narrow vocabulary tile, one K slab
+    (300, 20, 64, 520, 1),      # more sequences than the planning pass scans at once; several row groups
+    (40, 260, 128, 300, 100),   # several row groups of several tiles each
+    (1, 8, 8, 1, 1),            # smallest legal D, one vocabulary entry
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
     print(run_case(inp))
+
+
+def test_forward_beyond_the_backward_length_limit():
+    # S above 8192 is forward-only
+    inp = wl.make_custom(2, 9000, 64, 40, seed=31, len_lo=8000, backward=False)
+    print(run_case(inp, check_bwd=False))
 
 
 def test_fp32_small_shapes():
