@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE / WRITE_SIZE runs of this same script (summaries: profiles/c5_hbm_counters.txt).
 # FETCH_SIZE is scaled by 2.00 and WRITE_SIZE by 1.00, the factors a 1 GiB copy gives (--calib-copy).
 MEASURED_FWD_TRAFFIC_BYTES = {
-    "c5_large_fwdbwd": int((6393116 * 2.00 + 125743 * 1.00) * 1024),
+    "c5_large_fwdbwd": int((7653140 * 2.00 + 125804 * 1.00) * 1024),
 }
 
 
@@ -135,6 +135,29 @@ def cpu_baseline(inp, n_rows, np):
                       f"all {w.B} sequences, forward+backward in fp64"}
 
 
+def vendor_gemm_reference(torch, inp, n_cols=32768, iters=10):
+    """Context, not part of the path: the vendor bf16 GEMM (torch.matmul -> hipBLASLt) on the packed
+    valid-token matrix against one 32768-column slab of the vocabulary, i.e. the GEMM a
+    library-GEMM-plus-reduce design (Alg. 2) would run per slab, logits written to memory."""
+    w = inp.workload
+    M, K, N = int(inp.sum_len), w.D, min(n_cols, w.V)
+    a = torch.randn(M, K, device="cuda:0", dtype=torch.bfloat16)
+    b = torch.randn(N, K, device="cuda:0", dtype=torch.bfloat16) * 0.02
+    for _ in range(3):
+        c = a @ b.t()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        c = a @ b.t()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    del a, b, c
+    return {"M": M, "N": N, "K": K, "ms": ms, "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12,
+            "note": "library GEMM alone, bf16 logits written to HBM; no max/argmax/activation"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -167,7 +190,7 @@ def main():
             "algorithmic_bytes": int(w.B * w.S * w.D * 2 + w.V * w.D * 2 + w.B * w.V * 8 + w.V * 4),
             "flops_per_launch": fwd_flops, "avg_launch_ms": res["fwd_ms"],
             "note": "flops count valid tokens only; the launch time is the forward call "
-                    "(mask compaction, ~4 us, + the fused kernel) from events on the launch stream"}
+                    "(three planning kernels, ~13 us, + the fused kernel) from events on the launch stream"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     del head
     torch.cuda.empty_cache()
@@ -182,6 +205,7 @@ def main():
             del h
             torch.cuda.empty_cache()
 
+    vendor = None if args.no_extra else vendor_gemm_reference(torch, inp)
     cpu = None if args.no_cpu else cpu_baseline(inp, args.cpu_rows, np)
 
     if args.calib_copy:
@@ -203,6 +227,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "detail": res,
+        "vendor_gemm_reference": vendor,
         "other_workloads": extra,
     }
     print(json.dumps(out))
