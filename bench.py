@@ -166,7 +166,7 @@ def main():
     ap.add_argument("--workload", default="c5_large_fwdbwd")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy (reference reading for rocprofv3 byte counters)")
     args = ap.parse_args()

@@ -194,6 +194,20 @@ __device__ __forceinline__ void dma4_to_lds(const void* gptr, uint32_t lds_base)
                  : "v"(gptr), "s"(lds_base)
                  : "memory", "m0");
 }
+// The same two loads addressed as wave-uniform base (an SGPR pair) + 32-bit byte offset per lane:
+// no 64-bit address arithmetic per load, and half the address registers.
+__device__ __forceinline__ void dma16_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void dma4_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));   // LDS aperture: low 32 bits are the offset
 }
@@ -210,7 +224,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 //                        barriers, load waits and epilogues)
 // PMRING  the per-block maxima of the epilogue live in a ring stage that is idle by then instead of
 //         in LDS of their own (needed to fit two workgroups of three stages in 160 KB)
-template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int SPREAD = BK / 32>
+// L2PF  slabs of look-ahead for a cache prefetch of the operand rows (0 = none)
+template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int L2PF = 0, int SPREAD = BK / 32>
 __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams p) {
     static_assert(BK == 64 || BK == 32, "slab depth");
     static_assert(DMA || (BK == 64 && NS == 2 && NWN == 4), "register-staged loader: BK = 64, two stages, 8 waves");
@@ -253,6 +268,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     __shared__ __attribute__((aligned(64))) int s_meta[4][16];
     // per (block, column): max logit of the block and its position
     __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[PMRING ? 16 : 2 * PM_BYTES];
+    __shared__ __attribute__((aligned(256))) int s_sink[NW][64];        // landing pad of the cache prefetches
 
     // ---- workgroup -> (row group, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
@@ -286,13 +302,21 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     const int lp = lane % CPR;
     const int gch = lp ^ lds_swz<BK>(lrow);                   // swizzle bits do not depend on j
     const int st_off = lrow * RB + lp * 16;                   // + JSTEP j   (register-staged loader)
-    const uint16_t* wptr[IPB];
+    // Operand rows are addressed as base + byte offset; the direct-to-LDS loader keeps the offsets in
+    // 32 bits (the host takes this path only while H and W are each below 4 GiB).
+    size_t woff[DMA ? 1 : IPB];
+    uint32_t woff32[DMA ? IPB : 1];
 #pragma unroll
     for (int j = 0; j < IPB; ++j) {
         int v = v0 + lrow + NW * RPI * j;
         v = v < p.V ? v : p.V - 1;
-        wptr[j] = p.W + (size_t)v * D + gch * 8;
+        const size_t o = ((size_t)v * D + gch * 8) * 2;
+        if constexpr (DMA) woff32[j] = (uint32_t)o;
+        else woff[j] = o;
     }
+    const char* const Hb = reinterpret_cast<const char*>(p.H);
+    const char* const Wb = reinterpret_cast<const char*>(p.W);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(wave * 1024);
     // ---- fragment geometry ----
     // Tile blocks are interleaved between the two wave rows (wave row wm owns tile blocks
     // wm, wm+2, wm+4, wm+6), so that a short last tile splits evenly between them.
@@ -328,14 +352,34 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     const float bias_v = (tid < TN && v_out < p.V) ? p.bias[v_out] : 0.f;
     __syncthreads();
 
+    // Cache prefetch (L2PF > 0): one row per lane.  The first FWD_TM / 64 waves cover the token rows
+    // of the tile, the next TN / 64 the vocabulary rows; one 4-byte direct-to-LDS load per lane and
+    // slab pulls that row's 128-byte line of a later slab into L2 without holding a register.
+    uint32_t pfo = 0;
+    const bool pf_tokens = wave * 64 < FWD_TM;
+    if (L2PF > 0 && !pf_tokens) {
+        const int v = v0 + (wave * 64 - FWD_TM) + lane;
+        pfo = (uint32_t)((size_t)(v < p.V ? v : p.V - 1) * D * 2);
+    }
+    const uintptr_t pf_sel = reinterpret_cast<uintptr_t>(pf_tokens ? Hb : Wb);
+    const char* const pf_base = reinterpret_cast<const char*>(
+        ((uintptr_t)__builtin_amdgcn_readfirstlane((uint32_t)(pf_sel >> 32)) << 32) |
+        (uintptr_t)__builtin_amdgcn_readfirstlane((uint32_t)pf_sel));
+    const uint32_t sink = lds_addr(&s_sink[0][0]) + __builtin_amdgcn_readfirstlane(wave * 256);
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
         const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
         const bool has_next = t + 1 < n_tiles;
-        const uint16_t* hptr[IPA];
+        size_t hoff[DMA ? 1 : IPA];
+        uint32_t hoff32[DMA ? IPA : 1];
 #pragma unroll
-        for (int j = 0; j < IPA; ++j) hptr[j] = p.H + (size_t)s_rows[buf][lrow + NW * RPI * j].x * D + gch * 8;
+        for (int j = 0; j < IPA; ++j) {
+            const size_t o = ((size_t)s_rows[buf][lrow + NW * RPI * j].x * D + gch * 8) * 2;
+            if constexpr (DMA) hoff32[j] = (uint32_t)o;
+            else hoff[j] = o;
+        }
+        if (L2PF > 0 && wave * 64 < FWD_TM) pfo = (uint32_t)((size_t)s_rows[buf][wave * 64 + lane].x * D * 2);
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(t + 1, buf ^ 1);
 
@@ -352,10 +396,10 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
             // (lane l lands at +16 l); the wave-uniform base goes through M0.
             // load n (0 .. LPT-1) of slab kt into ring stage ST: first the A rows, then the B rows
             auto issue_one = [&](auto st, int kt, int n) {
-                const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr(ring(st)) + wave * 1024);
-                const int koff = kt * BK;
-                if (n < IPA) dma16_to_lds(hptr[n] + koff, dst + n * JSTEP);
-                else dma16_to_lds(wptr[n - IPA] + koff, dst + SLAB_A + (n - IPA) * JSTEP);
+                const uint32_t dst = lds_addr(ring(st)) + wave_lds;
+                const int kbytes = kt * (BK * 2);
+                if (n < IPA) dma16_to_lds(Hb + kbytes, hoff32[n], dst + n * JSTEP);
+                else dma16_to_lds(Wb + kbytes, woff32[n - IPA], dst + SLAB_A + (n - IPA) * JSTEP);
             };
             auto issue = [&](auto st, int kt) {
 #pragma unroll
@@ -374,6 +418,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                     const int ahead = min(nk - 1 - kt, NS - 2);
                     if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
                     else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
+                    else if (L2PF > 0 && kt > 0) wait_vmcnt<1>();    // the prefetch behind them may stay out
                     else wait_vmcnt<0>();
                     __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
                     const bool more = kt + NS - 1 < nk;
@@ -387,6 +432,10 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                         const uint8_t* sa = ring(st) + fa_row * RB;
                         const uint8_t* sb = ring(st) + SLAB_A + fb_row * RB;
                         mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
+                    }
+                    if constexpr (L2PF > 0) {
+                        static_assert(NS == 2 && BK == 64 && NW * 64 == FWD_TM + TN, "prefetch assumes one line per row and slab");
+                        dma4_to_lds(pf_base + min(kt + L2PF, nk - 1) * (BK * 2), pfo, sink);
                     }
                 };
                 if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
@@ -414,17 +463,17 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                 const int koff = kt * BK;
                 if (koff + BK <= D) {
 #pragma unroll
-                    for (int j = 0; j < IPA; ++j) ra[j] = *reinterpret_cast<const uint4*>(hptr[j] + koff);
+                    for (int j = 0; j < IPA; ++j) ra[j] = *reinterpret_cast<const uint4*>(Hb + hoff[j] + koff * 2);
 #pragma unroll
-                    for (int j = 0; j < IPB; ++j) rb[j] = *reinterpret_cast<const uint4*>(wptr[j] + koff);
+                    for (int j = 0; j < IPB; ++j) rb[j] = *reinterpret_cast<const uint4*>(Wb + woff[j] + koff * 2);
                 } else {
                     const bool kval = koff + gch * 8 < D;
 #pragma unroll
                     for (int j = 0; j < IPA; ++j)
-                        ra[j] = kval ? *reinterpret_cast<const uint4*>(hptr[j] + koff) : make_uint4(0, 0, 0, 0);
+                        ra[j] = kval ? *reinterpret_cast<const uint4*>(Hb + hoff[j] + koff * 2) : make_uint4(0, 0, 0, 0);
 #pragma unroll
                     for (int j = 0; j < IPB; ++j)
-                        rb[j] = kval ? *reinterpret_cast<const uint4*>(wptr[j] + koff) : make_uint4(0, 0, 0, 0);
+                        rb[j] = kval ? *reinterpret_cast<const uint4*>(Wb + woff[j] + koff * 2) : make_uint4(0, 0, 0, 0);
                 }
             };
             auto lstore = [&](int st) {
