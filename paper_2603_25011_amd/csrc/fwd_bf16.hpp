@@ -194,16 +194,10 @@ __device__ __forceinline__ void dma4_to_lds(const void* gptr, uint32_t lds_base)
                  : "v"(gptr), "s"(lds_base)
                  : "memory", "m0");
 }
-// The same two loads addressed as wave-uniform base (an SGPR pair) + 32-bit byte offset per lane:
+// The 16-byte load addressed as wave-uniform base (an SGPR pair) + 32-bit byte offset per lane:
 // no 64-bit address arithmetic per load, and half the address registers.
 __device__ __forceinline__ void dma16_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff), "s"(sbase), "s"(lds_base)
-                 : "memory", "m0");
-}
-__device__ __forceinline__ void dma4_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_base)
                  : "memory", "m0");
@@ -224,8 +218,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 //                        barriers, load waits and epilogues)
 // PMRING  the per-block maxima of the epilogue live in a ring stage that is idle by then instead of
 //         in LDS of their own (needed to fit two workgroups of three stages in 160 KB)
-// L2PF  slabs of look-ahead for a cache prefetch of the operand rows (0 = none)
-template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int L2PF = 0, int SPREAD = BK / 32>
+template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int SPREAD = BK / 32>
 __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams p) {
     static_assert(BK == 64 || BK == 32, "slab depth");
     static_assert(DMA || (BK == 64 && NS == 2 && NWN == 4), "register-staged loader: BK = 64, two stages, 8 waves");
@@ -268,7 +261,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     __shared__ __attribute__((aligned(64))) int s_meta[4][16];
     // per (block, column): max logit of the block and its position
     __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[PMRING ? 16 : 2 * PM_BYTES];
-    __shared__ __attribute__((aligned(256))) int s_sink[NW][64];        // landing pad of the cache prefetches
 
     // ---- workgroup -> (row group, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
@@ -352,20 +344,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     const float bias_v = (tid < TN && v_out < p.V) ? p.bias[v_out] : 0.f;
     __syncthreads();
 
-    // Cache prefetch (L2PF > 0): one row per lane.  The first FWD_TM / 64 waves cover the token rows
-    // of the tile, the next TN / 64 the vocabulary rows; one 4-byte direct-to-LDS load per lane and
-    // slab pulls that row's 128-byte line of a later slab into L2 without holding a register.
-    uint32_t pfo = 0;
-    const bool pf_tokens = wave * 64 < FWD_TM;
-    if (L2PF > 0 && !pf_tokens) {
-        const int v = v0 + (wave * 64 - FWD_TM) + lane;
-        pfo = (uint32_t)((size_t)(v < p.V ? v : p.V - 1) * D * 2);
-    }
-    const uintptr_t pf_sel = reinterpret_cast<uintptr_t>(pf_tokens ? Hb : Wb);
-    const char* const pf_base = reinterpret_cast<const char*>(
-        ((uintptr_t)__builtin_amdgcn_readfirstlane((uint32_t)(pf_sel >> 32)) << 32) |
-        (uintptr_t)__builtin_amdgcn_readfirstlane((uint32_t)pf_sel));
-    const uint32_t sink = lds_addr(&s_sink[0][0]) + __builtin_amdgcn_readfirstlane(wave * 256);
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
@@ -379,7 +357,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
             if constexpr (DMA) hoff32[j] = (uint32_t)o;
             else hoff[j] = o;
         }
-        if (L2PF > 0 && wave * 64 < FWD_TM) pfo = (uint32_t)((size_t)s_rows[buf][wave * 64 + lane].x * D * 2);
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(t + 1, buf ^ 1);
 
@@ -418,7 +395,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                     const int ahead = min(nk - 1 - kt, NS - 2);
                     if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
                     else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
-                    else if (L2PF > 0 && kt > 0) wait_vmcnt<1>();    // the prefetch behind them may stay out
                     else wait_vmcnt<0>();
                     __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
                     const bool more = kt + NS - 1 < nk;
@@ -432,10 +408,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                         const uint8_t* sa = ring(st) + fa_row * RB;
                         const uint8_t* sb = ring(st) + SLAB_A + fb_row * RB;
                         mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
-                    }
-                    if constexpr (L2PF > 0) {
-                        static_assert(NS == 2 && BK == 64 && NW * 64 == FWD_TM + TN, "prefetch assumes one line per row and slab");
-                        dma4_to_lds(pf_base + min(kt + L2PF, nk - 1) * (BK * 2), pfo, sink);
                     }
                 };
                 if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
