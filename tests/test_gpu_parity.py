@@ -149,3 +149,28 @@ def test_c2_document_encoding_forward_full():
 def test_c3_query_encoding_forward_backward_full():
     inp = wl.make_inputs(wl.WORKLOADS["c3_query_fwdbwd"])
     print(run_case(inp))
+
+
+def test_autograd_wrapper_matches_direct_calls():
+    from paper_2603_25011_amd.autograd import lsr_head
+    inp = wl.make_custom(5, 70, 128, 640, seed=41, len_lo=3)
+    head = DeviceHead(inp)
+    head.forward()
+    head.backward()
+    torch.cuda.synchronize()
+    H = head.H.clone().requires_grad_(True)
+    W = head.W.clone().requires_grad_(True)
+    bias = head.bias.clone().requires_grad_(True)
+    Y, I = lsr_head(H, W, bias, head.mask)
+    assert torch.equal(Y, head.Y) and torch.equal(I, head.I)
+    Y.backward(head.dY)
+    torch.cuda.synchronize()
+    # same kernels, same order: float32 results are identical before the cast to the parameter dtype
+    assert torch.equal(H.grad, head.dH.to(torch.bfloat16))
+    assert torch.equal(W.grad, head.dW.to(torch.bfloat16))
+    assert torch.equal(bias.grad, head.db)
+    # only the bias needs a gradient: the other outputs are skipped
+    H2, W2, b2 = head.H.clone(), head.W.clone(), head.bias.clone().requires_grad_(True)
+    Y2, _ = lsr_head(H2, W2, b2, head.mask)
+    Y2.backward(head.dY)
+    assert torch.equal(b2.grad, head.db)
