@@ -51,7 +51,7 @@ typedef enum { LSR_F32 = 0, LSR_BF16 = 1 } lsr_dtype;
 /*
  * Problem shape (paper Sec. 2: H in R^{B x S x D}, E (here W) in R^{|V| x D}, b in R^{|V|},
  * M in {0,1}^{B x S}).  H and W share hw_dtype; bias, Y and all gradients are float32; I is int32.
- * Limits: 1 <= B,S,D,V;  B*S < 2^31;  B*V < 2^31;  D a multiple of 8 and D <= 8192;
+ * Limits: 1 <= B,S,D,V;  B <= 65535;  B*S < 2^31;  B*V < 2^31;  D a multiple of 8 and D <= 8192;
  * S <= 32768 (backward: S <= 8192 and B <= 6144).  LSR_BF16 runs the MFMA kernel; LSR_F32 is a
  * plain reference-precision path meant for small problems.
  */

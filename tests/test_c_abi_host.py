@@ -73,6 +73,13 @@ def test_forward_argument_errors_come_before_any_device_work(lib):
     with pytest.raises(lsr.LsrError) as e:
         _fwd((2, 16, 64, 1000, 5), good)
     assert e.value.status == 3
+    for bad in ((70000, 16, 64, 1000, lsr.LSR_BF16),        # B above 65535
+                (2, 40000, 64, 1000, lsr.LSR_BF16),         # S above 32768
+                (2, 16, 8200, 1000, lsr.LSR_BF16),          # D above 8192
+                (40000, 16, 64, 60000, lsr.LSR_BF16)):      # B*V at or above 2^31
+        with pytest.raises(lsr.LsrError) as e:
+            _fwd(bad, good)
+        assert e.value.status == 2, bad
     with pytest.raises(lsr.LsrError) as e:
         _fwd(shape, [4100] + good[1:])
     assert e.value.status == 4
