@@ -344,19 +344,26 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     const float bias_v = (tid < TN && v_out < p.V) ? p.bias[v_out] : 0.f;
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
-        const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
-        const bool has_next = t + 1 < n_tiles;
-        size_t hoff[DMA ? 1 : IPA];
-        uint32_t hoff32[DMA ? IPA : 1];
+    size_t hoff[DMA ? 1 : IPA];
+    uint32_t hoff32[DMA ? IPA : 1];
+    auto row_offsets = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < IPA; ++j) {
             const size_t o = ((size_t)s_rows[buf][lrow + NW * RPI * j].x * D + gch * 8) * 2;
             if constexpr (DMA) hoff32[j] = (uint32_t)o;
             else hoff[j] = o;
         }
+    };
+    bool prefetched = false;      // the first slab of the coming tile is already in flight
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
+        const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
+        const bool has_next = t + 1 < n_tiles;
+        // With two stages and an even slab count a tile ends in stage 1, so the first slab of the next
+        // tile can be requested into stage 0 from inside the last slab and flies during the epilogue.
+        const bool pf_next = DMA && NS == 2 && has_next && nk >= 2 && (nk & 1) == 0;
+        if (!prefetched) row_offsets(buf);
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(t + 1, buf ^ 1);
 
@@ -389,17 +396,20 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                 // One pipeline step for slab kt, which lives in stage ST (compile-time so that every
                 // LDS access names its stage's array).  The loads of slab kt + NS - 1 ride inside its
                 // MFMA stream.
-                auto step = [&](auto st, int kt) {
+                // (NEXT: this is the last slab of the tile and its loads are the first slab of the next
+                //  tile, whose row offsets the caller has already put in place)
+                auto step = [&](auto st, auto next_c, int kt) {
                     constexpr int ST = decltype(st)::value;
+                    constexpr bool NEXT = decltype(next_c)::value;
                     // slabs after kt that are already in flight may stay in flight
                     const int ahead = min(nk - 1 - kt, NS - 2);
                     if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
                     else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
                     else wait_vmcnt<0>();
                     __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
-                    const bool more = kt + NS - 1 < nk;
+                    const bool more = NEXT || kt + NS - 1 < nk;
                     auto dma = [&](int n) {
-                        if (more) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, kt + NS - 1, n);
+                        if (more) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, NEXT ? 0 : kt + NS - 1, n);
                     };
                     if constexpr (NA == 0) {        // no live row block in this wave: only its loads
 #pragma unroll
@@ -410,14 +420,23 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                         mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
                     }
                 };
-                if (0 < nk) issue(std::integral_constant<int, 0>{}, 0);
+                constexpr std::false_type no{};
+                if (0 < nk && !prefetched) issue(std::integral_constant<int, 0>{}, 0);
                 if (NS > 2 && 1 < nk) issue(std::integral_constant<int, 1 % NS>{}, 1);
                 if (NS > 3 && 2 < nk) issue(std::integral_constant<int, 2 % NS>{}, 2);
-                for (int kt = 0; kt < nk; kt += NS) {
-                    step(std::integral_constant<int, 0>{}, kt);
-                    if (kt + 1 < nk) step(std::integral_constant<int, 1 % NS>{}, kt + 1);
-                    if (NS > 2 && kt + 2 < nk) step(std::integral_constant<int, 2 % NS>{}, kt + 2);
-                    if (NS > 3 && kt + 3 < nk) step(std::integral_constant<int, 3 % NS>{}, kt + 3);
+                const int nk_body = pf_next ? nk - 2 : nk;     // the last pair of slabs is handled below
+                for (int kt = 0; kt < nk_body; kt += NS) {
+                    step(std::integral_constant<int, 0>{}, no, kt);
+                    if (kt + 1 < nk_body) step(std::integral_constant<int, 1 % NS>{}, no, kt + 1);
+                    if (NS > 2 && kt + 2 < nk_body) step(std::integral_constant<int, 2 % NS>{}, no, kt + 2);
+                    if (NS > 3 && kt + 3 < nk_body) step(std::integral_constant<int, 3 % NS>{}, no, kt + 3);
+                }
+                if constexpr (NS == 2) {
+                    if (pf_next) {
+                        step(std::integral_constant<int, 0>{}, no, nk - 2);      // requests slab nk-1
+                        row_offsets(buf ^ 1);                                    // this tile's are no longer needed
+                        step(std::integral_constant<int, 1>{}, std::true_type{}, nk - 1);
+                    }
                 }
             };
             switch (na) {
@@ -515,6 +534,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
         }
         if (nk < NS) wait_vmcnt<0>();     // the next tile's tables, if the slab loop was too short to wait for them
         __syncthreads();
+        prefetched = pf_next;
         // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
         //      the first TN threads take part; without PMRING the others go on to the next tile. ----
         if (tid < TN) {
