@@ -379,15 +379,18 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
             // Slab kt goes to ring stage kt % NS.  Each wave-wide load fills 1024 contiguous LDS bytes
             // (lane l lands at +16 l); the wave-uniform base goes through M0.
             // load n (0 .. LPT-1) of slab kt into ring stage ST: first the A rows, then the B rows
-            auto issue_one = [&](auto st, int kt, int n) {
+            // load n (0 .. LPT-1) of a slab into ring stage ST: first the A rows, then the B rows; hb and wb
+            // are the operand bases already advanced to the slab's K offset (wave-uniform, in SGPRs)
+            auto issue_one = [&](auto st, const char* hb, const char* wb, int n) {
                 const uint32_t dst = lds_addr(ring(st)) + wave_lds;
-                const int kbytes = kt * (BK * 2);
-                if (n < IPA) dma16_to_lds(Hb + kbytes, hoff32[n], dst + n * JSTEP);
-                else dma16_to_lds(Wb + kbytes, woff32[n - IPA], dst + SLAB_A + (n - IPA) * JSTEP);
+                if (n < IPA) dma16_to_lds(hb, hoff32[n], dst + n * JSTEP);
+                else dma16_to_lds(wb, woff32[n - IPA], dst + SLAB_A + (n - IPA) * JSTEP);
             };
             auto issue = [&](auto st, int kt) {
+                const char* hb = Hb + (size_t)kt * (BK * 2);
+                const char* wb = Wb + (size_t)kt * (BK * 2);
 #pragma unroll
-                for (int n = 0; n < LPT; ++n) issue_one(st, kt, n);
+                for (int n = 0; n < LPT; ++n) issue_one(st, hb, wb, n);
             };
             // The whole slab loop is instantiated once per count NA of live row blocks and the choice is
             // made per tile, outside the loop, so that each instance is straight-line MFMA code.
@@ -407,9 +410,14 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                     else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
                     else wait_vmcnt<0>();
                     __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
-                    const bool more = NEXT || kt + NS - 1 < nk;
+                    // one scalar flag and one pair of advanced bases per slab: what is left per load is
+                    // a scalar branch, the M0 write and the load itself
+                    const int more = __builtin_amdgcn_readfirstlane((NEXT || kt + NS - 1 < nk) ? 1 : 0);
+                    const size_t kbytes = (size_t)(NEXT ? 0 : kt + NS - 1) * (BK * 2);
+                    const char* hb = Hb + kbytes;
+                    const char* wb = Wb + kbytes;
                     auto dma = [&](int n) {
-                        if (more) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, NEXT ? 0 : kt + NS - 1, n);
+                        if (more != 0) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, hb, wb, n);
                     };
                     if constexpr (NA == 0) {        // no live row block in this wave: only its loads
 #pragma unroll
