@@ -174,3 +174,21 @@ def test_autograd_wrapper_matches_direct_calls():
     Y2, _ = lsr_head(H2, W2, b2, head.mask)
     Y2.backward(head.dY)
     assert torch.equal(b2.grad, head.db)
+
+
+def test_random_shapes_and_masks():
+    """Two dozen seeded random problems: odd sizes, D from the smallest legal value up, masks of any
+    density with empty sequences mixed in, both loaders (D a multiple of 64 or not)."""
+    rng = np.random.default_rng(20260325)
+    for case in range(24):
+        B = int(rng.integers(1, 41))
+        S = int(rng.integers(1, 301))
+        D = int(rng.choice([8, 16, 24, 64, 72, 128, 192, 200, 256]))
+        V = int(rng.integers(1, 1501))
+        keep = float(rng.choice([0.05, 0.3, 0.7, 1.0]))
+        inp = wl.make_custom(B, S, D, V, seed=5000 + case)
+        mask = wl.scattered_mask(rng, B, S, keep=keep)
+        if B > 2 and case % 3 == 0:
+            mask[int(rng.integers(0, B)), :] = 0
+        print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep}", flush=True)
+        run_case(inp, mask=mask)
