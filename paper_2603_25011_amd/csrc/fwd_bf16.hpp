@@ -160,6 +160,65 @@ __device__ __forceinline__ void mma_slab(const uint8_t* sa, int a_stride, const 
     }
 }
 
+// The direct-to-LDS pipeline runs its slabs rotated by one k-step against the barriers: the MFMAs
+// of a slab's LAST k-step are issued after the barrier that publishes the NEXT slab, from fragments
+// that were read before it, and the first fragments of the new slab are read behind them.  No wave
+// then waits on LDS right after a barrier, when all eight would do so at once with the matrix pipe
+// empty.  Fragment buffers (parity = k-step & 1, KS even) therefore live across calls.
+//   MODE 0  first slab of a tile: burst-read k-step 0, then k-steps 0 .. KS-2 (reading 1 .. KS-1)
+//   MODE 1  later slabs: k-step KS-1 of the previous slab (reading k-step 0 of this one), then
+//           k-steps 0 .. KS-2 (reading 1 .. KS-1)
+//   MODE 2  after the last slab of the tile: its k-step KS-1
+// The order of the MFMAs on every accumulator is the same as without the rotation.
+template <int NA, int KS, int MODE, int NDMA, int SPREAD, typename DmaFn>
+__device__ __forceinline__ void mma_rot(const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
+                                        const int (&fsw)[KS], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
+                                        floatx16 (&acc)[4][2], DmaFn&& dma) {
+    static_assert(KS % 2 == 0 && KS >= 2, "buffer parity must not depend on the slab");
+    constexpr int M = NA * 2;
+    constexpr int Q = SPREAD > 0 ? NDMA / SPREAD : 0;
+    constexpr int GROUPS = MODE == 0 ? KS - 1 : (MODE == 1 ? KS : 1);
+    if constexpr (MODE == 0) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) fb[0][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[0]);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[0]);
+    }
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int mk = MODE == 0 ? g : (MODE == 1 ? (g == 0 ? KS - 1 : g - 1) : KS - 1);   // k-step multiplied
+        const int rk = MODE == 0 ? g + 1 : (MODE == 1 ? g : -1);                           // k-step read
+        const int cur = mk & 1, nxt = rk & 1;
+        auto read_next = [&](int q) {
+            if (rk >= 0 && q < NA + 2) {
+                if (q == 0 || q == 2) {
+                    const int c = q >> 1;
+                    fb[nxt][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[rk < 0 ? 0 : rk]);
+                } else {
+                    const int i = q == 1 ? 0 : q - 2;
+                    fa[nxt][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[rk < 0 ? 0 : rk]);
+                }
+            }
+        };
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            acc[m >> 1][m & 1] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m >> 1], fb[cur][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
+            read_next(m);
+            if (m == M - 1) {
+#pragma unroll
+                for (int q = M; q < NA + 2; ++q) read_next(q);
+            }
+            if (MODE != 2 && g < SPREAD) {
+                const int lo = (m * Q + M - 1) / M, hi = ((m + 1) * Q + M - 1) / M;
+#pragma unroll
+                for (int t = lo; t < hi; ++t) dma(g * Q + t);
+            }
+            __builtin_amdgcn_sched_barrier(0);      // keep this interleaving
+        }
+    }
+}
+
 template <int KS, bool PF, int NDMA, int SPREAD, typename DmaFn>
 __device__ __forceinline__ void mma_dispatch(int na, const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
                                              const int (&fsw)[KS], floatx16 (&acc)[4][2], DmaFn&& dma) {
@@ -396,28 +455,29 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
             // made per tile, outside the loop, so that each instance is straight-line MFMA code.
             auto run_slabs = [&](auto na_c) {
                 constexpr int NA = decltype(na_c)::value;
-                // One pipeline step for slab kt, which lives in stage ST (compile-time so that every
-                // LDS access names its stage's array).  The loads of slab kt + NS - 1 ride inside its
-                // MFMA stream.
+                static_assert(NS == 2, "the rotated pipeline is written for two stages");
+                bf16x8 fa[2][4], fb[2][2];
+                // One pipeline step: barrier that publishes slab kt (stage ST), then a slab's worth of
+                // MFMAs (see mma_rot) with the loads of slab kt + 1 riding inside them.
                 // (NEXT: this is the last slab of the tile and its loads are the first slab of the next
                 //  tile, whose row offsets the caller has already put in place)
-                auto step = [&](auto st, auto next_c, int kt) {
+                auto step = [&](auto st, auto mode_c, auto next_c, int kt) {
                     constexpr int ST = decltype(st)::value;
+                    constexpr int MODE = decltype(mode_c)::value;
                     constexpr bool NEXT = decltype(next_c)::value;
-                    // slabs after kt that are already in flight may stay in flight
-                    const int ahead = min(nk - 1 - kt, NS - 2);
-                    if (NS >= 4 && ahead == 2) wait_vmcnt<2 * LPT>();
-                    else if (NS >= 3 && ahead == 1) wait_vmcnt<LPT>();
-                    else wait_vmcnt<0>();
-                    __syncthreads();    // slab kt has landed for every wave; stage (kt-1) % NS is free
+                    // every fragment read of the previous slab has returned (its stage is about to be
+                    // reloaded by whoever leaves the barrier first) and slab kt has landed
+                    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+                    wait_vmcnt<0>();
+                    __syncthreads();
                     // one scalar flag and one pair of advanced bases per slab: what is left per load is
                     // a scalar branch, the M0 write and the load itself
-                    const int more = __builtin_amdgcn_readfirstlane((NEXT || kt + NS - 1 < nk) ? 1 : 0);
-                    const size_t kbytes = (size_t)(NEXT ? 0 : kt + NS - 1) * (BK * 2);
+                    const int more = __builtin_amdgcn_readfirstlane((NEXT || kt + 1 < nk) ? 1 : 0);
+                    const size_t kbytes = (size_t)(NEXT ? 0 : kt + 1) * (BK * 2);
                     const char* hb = Hb + kbytes;
                     const char* wb = Wb + kbytes;
                     auto dma = [&](int n) {
-                        if (more != 0) issue_one(std::integral_constant<int, (ST + NS - 1) % NS>{}, hb, wb, n);
+                        if (more != 0) issue_one(std::integral_constant<int, (ST + 1) % NS>{}, hb, wb, n);
                     };
                     if constexpr (NA == 0) {        // no live row block in this wave: only its loads
 #pragma unroll
@@ -425,26 +485,28 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                     } else {
                         const uint8_t* sa = ring(st) + fa_row * RB;
                         const uint8_t* sb = ring(st) + SLAB_A + fb_row * RB;
-                        mma_slab<NA, KS, true, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, acc, dma);
+                        mma_rot<NA, KS, MODE, LPT, SPREAD>(sa, A_STRIDE, sb, B_STRIDE, fsw, fa, fb, acc, dma);
                     }
                 };
                 constexpr std::false_type no{};
-                if (0 < nk && !prefetched) issue(std::integral_constant<int, 0>{}, 0);
-                if (NS > 2 && 1 < nk) issue(std::integral_constant<int, 1 % NS>{}, 1);
-                if (NS > 3 && 2 < nk) issue(std::integral_constant<int, 2 % NS>{}, 2);
-                const int nk_body = pf_next ? nk - 2 : nk;     // the last pair of slabs is handled below
-                for (int kt = 0; kt < nk_body; kt += NS) {
-                    step(std::integral_constant<int, 0>{}, no, kt);
-                    if (kt + 1 < nk_body) step(std::integral_constant<int, 1 % NS>{}, no, kt + 1);
-                    if (NS > 2 && kt + 2 < nk_body) step(std::integral_constant<int, 2 % NS>{}, no, kt + 2);
-                    if (NS > 3 && kt + 3 < nk_body) step(std::integral_constant<int, 3 % NS>{}, no, kt + 3);
+                constexpr std::integral_constant<int, 0> first{};
+                constexpr std::integral_constant<int, 1> steady{};
+                constexpr std::integral_constant<int, 0> st0{};
+                constexpr std::integral_constant<int, 1> st1{};
+                if (!prefetched) issue(st0, 0);
+                step(st0, first, no, 0);
+                const int n_end = pf_next ? nk - 1 : nk;      // steady steps without a successor tile: 1 .. n_end-1
+                for (int kt = 1; kt < n_end; kt += 2) {
+                    step(st1, steady, no, kt);
+                    if (kt + 1 < n_end) step(st0, steady, no, kt + 1);
                 }
-                if constexpr (NS == 2) {
-                    if (pf_next) {
-                        step(std::integral_constant<int, 0>{}, no, nk - 2);      // requests slab nk-1
-                        row_offsets(buf ^ 1);                                    // this tile's are no longer needed
-                        step(std::integral_constant<int, 1>{}, std::true_type{}, nk - 1);
-                    }
+                if (pf_next) {                                // nk is even: slab nk-1 lives in stage 1
+                    row_offsets(buf ^ 1);                     // this tile's are no longer needed
+                    step(st1, steady, std::true_type{}, nk - 1);
+                }
+                if constexpr (NA > 0) {                       // last k-step of the last slab
+                    const uint8_t* dummy = ring(st0);
+                    mma_rot<NA, KS, 2, LPT, SPREAD>(dummy, A_STRIDE, dummy, B_STRIDE, fsw, fa, fb, acc, [](int) {});
                 }
             };
             switch (na) {
