@@ -204,10 +204,17 @@ __device__ __forceinline__ void mma_rot(const uint8_t* sa, int a_stride, const u
         for (int m = 0; m < M; ++m) {
             acc[m >> 1][m & 1] =
                 __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m >> 1], fb[cur][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
-            read_next(m);
-            if (m == M - 1) {
+            if (rk == KS - 1) {
+                // the reads before a barrier have to be back when the wave reaches it: two per MFMA,
+                // so that the last one still has most of the group to return
+                read_next(2 * m);
+                read_next(2 * m + 1);
+            } else {
+                read_next(m);
+                if (m == M - 1) {
 #pragma unroll
-                for (int q = M; q < NA + 2; ++q) read_next(q);
+                    for (int q = M; q < NA + 2; ++q) read_next(q);
+                }
             }
             if (MODE != 2 && g < SPREAD) {
                 const int lo = (m * Q + M - 1) / M, hi = ((m + 1) * Q + M - 1) / M;
