@@ -61,7 +61,9 @@ typedef struct {
 } lsr_head_desc;
 
 /* Bytes of device scratch the forward (for_backward = 0) or backward (!= 0) call needs for
- * this shape: O(B*S) for the forward, O(B*V) for the backward.  Returns 0 for an invalid desc. */
+ * this shape: O(B*S) for the forward, O(B*V + B*S) for the backward (8*B*V bytes of sorted
+ * (v, g) pairs, count tables of at most 4*B*V, and 4*B*S*(c+1) for a vocabulary gathered in
+ * c <= 64 chunks).  Returns 0 for an invalid desc. */
 size_t lsr_head_workspace_bytes(const lsr_head_desc* desc, int for_backward);
 
 /*

@@ -170,7 +170,8 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// dH[b,s,:] = sum over the bucket of (b,s), in ascending v, of g * W[v,:].   grid (S, B)
+// dH[b,s,:] = sum over the bucket of (b,s), in ascending v, of g * W[v,:].   grid (B, S): b fastest,
+// so that the empty buckets behind the ends of the sequences are spread evenly over the chip
 // ---------------------------------------------------------------------------------------------
 template <typename T, int CPT>
 __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict__ W,
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict
     constexpr int N = RowChunk<T>::N;
     __shared__ int s_v[ROW_THREADS];
     __shared__ float s_g[ROW_THREADS];
-    const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int b = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
     const int n_chunks = D / N;
     const int beg = bstart[(size_t)b * (S + 1) + s];
     const int end = bstart[(size_t)b * (S + 1) + s + 1];
@@ -433,37 +434,86 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
 
 // ---------------------------------------------------------------------------------------------
 // dH, column-sliced variant (D a multiple of 64).
-// Buckets are sorted by v, and buckets that run at the same time walk the vocabulary at the same
-// pace, so at any moment the chip gathers rows of W from a moving window of the vocabulary.  With
-// whole rows that window is tens of MB (memory-side cache or HBM); cut into 64-column slices, with
-// the grid ordered slice-major, it is a few MB and lives in L2.  One wave owns one bucket and one
-// slice: a 64-column piece of a row is LPR lanes x 16 bytes, so the wave gathers 64/LPR bucket
-// entries per load, keeps four loads in flight per lane, and folds the per-entry partial sums with
-// a fixed butterfly at the end (reproducible order).   grid = ceil(B*S/4) * (D/64), 256 threads.
+// One sub-group of a wave owns one bucket and one 64-column slice; the grid is ordered slice-major.
+// A 64-column piece of a row is LPR lanes x 16 bytes, so a sub-group of G = 64/BPW lanes gathers
+// G/LPR bucket entries per load, keeps four loads in flight per lane, and folds the per-entry
+// partial sums with a fixed butterfly at the end (reproducible order).
+//
+// What decides the speed is whether the rows of W being gathered come from L2.  All buckets walk the
+// vocabulary in ascending v but not in step, so the working set of one slice pass is the whole slice
+// of W: |V| x 128 bytes.  Up to about 4 MB that lives in L2; beyond, the vocabulary is cut into n_vc
+// chunks and the pass is launched once per chunk (`vc` = chunk index), each launch gathering only
+// the entries of its chunk.  `bounds` then holds, per bucket, the n_vc+1 positions in the sorted
+// entry list where the chunks begin (bwd_chunk_bounds_kernel); with n_vc = 1 it is the bucket start
+// table itself.  Chunk 0 writes dH (zeros for empty buckets), later chunks add to it: one owner per
+// element and launch, launches in stream order, so the sum keeps a fixed order.
+// grid = B * ceil(S / (4*BPW)) * (D/64), 256 threads.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+__global__ __launch_bounds__(256) void bwd_chunk_bounds_kernel(const int* __restrict__ bstart,
+                                                               const uint2* __restrict__ perm,
+                                                               int* __restrict__ bounds,
+                                                               int n_buckets, int S, int V, int n_vc, int vc_len) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)n_buckets * (n_vc + 1)) return;
+    const int bucket = (int)(idx / (n_vc + 1));
+    const int c = (int)(idx - (long long)bucket * (n_vc + 1));
+    const int b = bucket / S, s = bucket - b * S;
+    int lo = bstart[(size_t)b * (S + 1) + s];
+    int hi = bstart[(size_t)b * (S + 1) + s + 1];
+    if (c == n_vc) lo = hi;
+    const unsigned target = (unsigned)c * (unsigned)vc_len;     // first v of chunk c
+    const uint2* list = perm + (size_t)b * V;
+    while (lo < hi) {                                           // first entry with v >= target
+        const int mid = lo + ((hi - lo) >> 1);
+        if (list[mid].x < target) lo = mid + 1; else hi = mid;
+    }
+    bounds[idx] = lo;
+}
+
+template <typename T, int BPW>
 __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict__ W,
-                                                            const int* __restrict__ bstart,
+                                                            const int* __restrict__ bounds,
                                                             const uint2* __restrict__ perm,
                                                             float* __restrict__ dH,
-                                                            int B, int S, int D, int V, int n_groups) {
+                                                            int B, int S, int D, int V, int n_groups,
+                                                            int n_vc, int vc) {
     constexpr int N = RowChunk<T>::N;
     constexpr int LPR = DWS_COLS / N;          // lanes per row piece
-    constexpr int EPW = 64 / LPR;              // bucket entries a wave gathers per load
+    constexpr int G = 64 / BPW;                // lanes per bucket
+    constexpr int EPG = G / LPR;               // entries of one bucket gathered per load
+    static_assert(EPG >= 1, "a bucket needs at least one row piece worth of lanes");
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int dc = blockIdx.x / n_groups;                          // slice-major order
-    const int bucket = (blockIdx.x - dc * n_groups) * 4 + wave;    // = b*S + s
-    if (bucket >= B * S) return;
-    const int b = bucket / S, s = bucket - b * S;
-    const int beg = bstart[(size_t)b * (S + 1) + s];
-    const int end = bstart[(size_t)b * (S + 1) + s + 1];
+    // Within a slice, consecutive workgroups take the same positions of consecutive sequences
+    // (b fastest).  Workgroups are dealt to the chip's shader engines in a fixed rotation; with s
+    // fastest, the empty buckets behind the end of each sequence recur with a period that can leave
+    // some engines with twice the work of others.
+    const int g = blockIdx.x - dc * n_groups;
+    const int b = g % B;
+    const int s = ((g / B) * 4 + wave) * BPW + lane / G;
+    const bool live = s < S;
+    const int bq = live ? b * S + s : 0;
+    const size_t bi = n_vc == 1 ? (size_t)b * (S + 1) + s : (size_t)bq * (n_vc + 1) + vc;
+    const int beg = live ? bounds[bi] : 0;
+    const int end = live ? bounds[bi + 1] : 0;
+    const bool add = vc > 0;
+    if (add && !__any(beg < end)) return;      // nothing of this chunk in any bucket of the wave
     const size_t prow = (size_t)b * V;
     const int col0 = dc * DWS_COLS + (lane % LPR) * N;
-    const int sub = lane / LPR;
+    const int sub = (lane % G) / LPR;
+    const bool writer = live && sub == 0 && (!add || beg < end);
+    float* out = dH + (size_t)bq * D + col0;
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    float4 prev[N / 4];                        // the sum of the earlier chunks, requested early
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) prev[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (add && writer) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) prev[i] = *reinterpret_cast<const float4*>(out + 4 * i);
+    }
     // the (v, g) entries of the next four loads are fetched while the current rows are in flight, so
     // the list read and the row gather it feeds never sit in one dependency chain
     int nv[4];
@@ -471,7 +521,7 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
     auto fetch_entries = [&](int base) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int k = base + u * EPW + sub;
+            const int k = base + u * EPG + sub;
             const bool ok = k < end;
             const uint2 ent = ok ? perm[prow + k] : make_uint2(0u, 0u);
             nv[u] = (int)ent.x;
@@ -479,7 +529,7 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
         }
     };
     fetch_entries(beg);
-    for (int base = beg; base < end; base += 4 * EPW) {
+    for (int base = beg; base < end; base += 4 * EPG) {
         float g[4];
         uint4 x[4];
 #pragma unroll
@@ -488,19 +538,20 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
             x[u] = make_uint4(0, 0, 0, 0);
             if (g[u] != 0.f) x[u] = *reinterpret_cast<const uint4*>(W + (size_t)nv[u] * D + col0);
         }
-        fetch_entries(base + 4 * EPW);
+        fetch_entries(base + 4 * EPG);
 #pragma unroll
         for (int u = 0; u < 4; ++u) RowChunk<T>::fma(x[u], g[u], acc);
     }
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1)
+    for (int off = LPR; off < G; off <<= 1)
 #pragma unroll
         for (int i = 0; i < N; ++i) acc[i] += __shfl_xor(acc[i], off);
-    if (sub == 0) {
-        float* out = dH + (size_t)bucket * D + col0;
+    if (writer) {
 #pragma unroll
-        for (int i = 0; i < N; i += 4)
-            *reinterpret_cast<float4*>(out + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+        for (int i = 0; i < N / 4; ++i)
+            *reinterpret_cast<float4*>(out + 4 * i) =
+                make_float4(prev[i].x + acc[4 * i], prev[i].y + acc[4 * i + 1], prev[i].z + acc[4 * i + 2],
+                            prev[i].w + acc[4 * i + 3]);
     }
 }
 

@@ -70,8 +70,26 @@ int fwd_row_groups(const Shape& s) {
     return (int)ng;
 }
 
-// ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] ----
-struct BwdWs { int n_seg, seg_len, key_bits; size_t perm_off, cnt_off, bs_off, total; };
+// ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] |
+//      bounds[B*S*(n_vc+1)] (only when the dH gather is cut into n_vc > 1 vocabulary chunks) ----
+struct BwdWs { int n_seg, seg_len, key_bits, n_vc, vc_len; size_t perm_off, cnt_off, bs_off, cb_off, total; };
+
+// Vocabulary chunks of the sliced dH gather.  A chunk is sized so that one 64-column slice of its
+// rows of W is about 4 MB (what stays in L2 while every bucket gathers from it).  Each chunk after
+// the first re-reads and re-writes dH once (8*B*S*D bytes), so the count is capped where that
+// traffic would pass a quarter of the gather traffic itself (B*|V|*D elements): long sequences
+// with few entries per bucket are gathered in one pass.
+void dh_chunks(const Shape& s, int* n_vc, int* vc_len) {
+    const long esize = s.dtype == LSR_F32 ? 4 : 2;
+    const long rows_l2 = (4l << 20) / (DWS_COLS * esize);
+    long c = (s.V + rows_l2 - 1) / rows_l2;
+    const long cap = (long)s.V * esize / (32l * s.S);
+    if (c > cap) c = cap;
+    if (c > 64) c = 64;
+    if (c < 1 || s.D % DWS_COLS != 0) c = 1;
+    *n_vc = (int)c;
+    *vc_len = (int)((s.V + c - 1) / c);
+}
 BwdWs bwd_ws(const Shape& s) {
     BwdWs w;
     // enough (b, segment) waves to fill the chip, segments of at least 512 entries, and a count
@@ -89,7 +107,9 @@ BwdWs bwd_ws(const Shape& s) {
     w.perm_off = 0;
     w.cnt_off = w.perm_off + align_up(sizeof(uint2) * bv);
     w.bs_off = w.cnt_off + align_up(sizeof(int) * (size_t)s.B * w.n_seg * s.S);
-    w.total = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
+    w.cb_off = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
+    dh_chunks(s, &w.n_vc, &w.vc_len);
+    w.total = w.cb_off + (w.n_vc > 1 ? align_up(sizeof(int) * (size_t)s.B * s.S * (w.n_vc + 1)) : 0);
     return w;
 }
 
@@ -339,17 +359,29 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(3);
         if (s.D % DWS_COLS == 0) {
-            // column-sliced gathers: the moving window of W rows stays in L2
-            const int n_groups = (s.B * s.S + 3) / 4;
+            // column-sliced gathers, one launch per vocabulary chunk: the rows of W in use stay in L2
+            const int* bounds = bstart;
+            if (w.n_vc > 1) {
+                int* cb = reinterpret_cast<int*>(base + w.cb_off);
+                const long long n = (long long)s.B * s.S * (w.n_vc + 1);
+                hipLaunchKernelGGL(bwd_chunk_bounds_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bstart, perm, cb,
+                                   s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
+                bounds = cb;
+            }
+            // a wave serves one bucket when it walks the bucket's whole list, two when it walks one chunk of it
+            const int bpw = w.n_vc > 1 ? 2 : 1;
+            const int n_groups = s.B * ((s.S + 4 * bpw - 1) / (4 * bpw));
+            if ((long long)n_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
             const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
-            if (s.dtype == LSR_F32)
-                hipLaunchKernelGGL((bwd_dh_sliced_kernel<float>), grid, dim3(256), 0, st, static_cast<const float*>(W), bstart,
-                                   perm, dH, s.B, s.S, s.D, s.V, n_groups);
-            else
-                hipLaunchKernelGGL((bwd_dh_sliced_kernel<uint16_t>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(W),
-                                   bstart, perm, dH, s.B, s.S, s.D, s.V, n_groups);
+            for (int vc = 0; vc < w.n_vc; ++vc) {
+#define LSR_DH(T, BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW>), grid, dim3(256), 0, st, static_cast<const T*>(W), bounds, \
+                                          perm, dH, s.B, s.S, s.D, s.V, n_groups, w.n_vc, vc)
+                if (s.dtype == LSR_F32) { if (bpw == 1) LSR_DH(float, 1); else LSR_DH(float, 2); }
+                else { if (bpw == 1) LSR_DH(uint16_t, 1); else LSR_DH(uint16_t, 2); }
+#undef LSR_DH
+            }
         } else {
-            const dim3 grid(s.S, s.B);
+            const dim3 grid(s.B, s.S);
             if (s.dtype == LSR_F32) launch_dh<float>(cpt, grid, st, static_cast<const float*>(W), bstart, perm, dH, s.S, s.D, s.V);
             else launch_dh<uint16_t>(cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm, dH, s.S, s.D, s.V);
         }

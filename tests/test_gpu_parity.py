@@ -55,6 +55,7 @@ def test_c1_tiny_fp32_forward_backward():
     (300, 20, 64, 520, 1),      # more sequences than the planning pass scans at once; several row groups
     (40, 260, 128, 300, 100),   # several row groups of several tiles each
     (1, 8, 8, 1, 1),            # smallest legal D, one vocabulary entry
+    (2, 16, 128, 70000, 1),     # vocabulary wide enough that the dH gather runs in three vocabulary chunks
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
@@ -69,6 +70,8 @@ def test_forward_beyond_the_backward_length_limit():
 
 def test_fp32_small_shapes():
     print(run_case(wl.make_custom(3, 20, 72, 333, dtype="f32", seed=5, w_std=0.05)))
+    # D a multiple of 64 and a vocabulary of three dH chunks
+    print(run_case(wl.make_custom(3, 20, 64, 40000, dtype="f32", seed=6, w_std=0.05)))
 
 
 def test_scattered_mask_and_empty_rows():
