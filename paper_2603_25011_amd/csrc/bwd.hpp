@@ -338,13 +338,20 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // L2 (the host sizes a group of NDC consecutive slices to about 3 MiB of H and a workgroup walks the
 // slices of its group, so that the (g, I) staging is not repeated more often than needed).
 // A row piece is 64 elements = LPR lanes x 16 bytes; a wave therefore serves 64/LPR vocabulary
-// rows at once, walks b = 0..B-1 for them with eight gathers in flight per lane, and writes one
-// 64-column piece of each dW row.  Summation order over b is fixed.
+// rows at once, walks the sequences that have a gradient for them with eight gathers in flight per
+// lane, and writes one 64-column piece of each dW row.  Summation order over b is fixed.
+// COMPACT (used for the narrow tiles of large batches, where sequences are short and gradients often
+// sparse): after staging, each column of the (g, I) tile is compacted in place to its non-zero
+// entries, in ascending b (one wave per column, ballot ranking) and closed by a zero, so that sparse
+// gradients cost what they hold; element (b, vv) of the tile then sits at word
+// b*VT + (vv ^ (b % VT)), so that staging (lanes along vv), compaction (lanes along b) and the gather
+// (eight columns per wave) all spread over the LDS banks.  Without it the tile is plain row-major
+// and every b is visited (measured 7 % faster on dense gradients).   VT a power of two.
 // dynamic LDS: B*VT floats + B*VT ints.   grid = ceil(V/VT) * ceil((D/64)/NDC).
 // ---------------------------------------------------------------------------------------------
 constexpr int DWS_COLS = 64;
 
-template <typename T>
+template <typename T, bool COMPACT>
 __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict__ H,
                                                             const float* __restrict__ dY,
                                                             const float* __restrict__ Y,
@@ -356,7 +363,8 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
     constexpr int VPG = 64 / LPR;              // vocabulary rows a wave serves at once
     extern __shared__ int s_dyn[];
     float* s_g = reinterpret_cast<float*>(s_dyn);          // [B][VT]
-    int* s_i = s_dyn + (size_t)B * VT;                     // [B][VT]
+    int* s_i = s_dyn + (size_t)B * VT;                     // [B][VT]  token row b*S + I[b,v]
+    auto at = [VT](int b, int vv) { return COMPACT ? b * VT + (vv ^ (b & (VT - 1))) : b * VT + vv; };
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -384,16 +392,43 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
         for (int u = 0; u < 4; ++u) {
             const int e = e0 + u * blockDim.x;
             if (e < B * VT) {
-                s_g[e] = gate_grad(dy[u], y[u]);
-                s_i[e] = clamp_pos(ix[u], S);
+                const int bb = e / VT, vv = e - bb * VT;
+                s_g[at(bb, vv)] = gate_grad(dy[u], y[u]);
+                s_i[at(bb, vv)] = bb * S + clamp_pos(ix[u], S);
             }
         }
     }
     __syncthreads();
 
+    // compaction: column vv keeps its non-zero entries, in ascending b, at rows 0..n-1, and a zero at
+    // row n if n < B.  A chunk of 64 rows is read before any of it is written and lands at or below
+    // where it was read, so this works in place.
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    for (int vv = wave; COMPACT && vv < VT; vv += n_waves) {
+        int n = 0;
+        for (int b0 = 0; b0 < B; b0 += 64) {
+            const int b = b0 + lane;
+            const float g = b < B ? s_g[at(b, vv)] : 0.f;
+            const int r = b < B ? s_i[at(b, vv)] : 0;
+            const unsigned long long nz = __ballot(g != 0.f);
+            if (g != 0.f) {
+                const int k = n + __popcll(nz & lt);
+                s_g[at(k, vv)] = g;
+                s_i[at(k, vv)] = r;
+            }
+            n += __popcll(nz);
+        }
+        if (lane == 0 && n < B) s_g[at(n, vv)] = 0.f;
+    }
+    if (COMPACT) __syncthreads();
+
     if (db && dg == 0 && tid < VT && v0 + tid < V) {           // fixed-order sum over b
         float sum = 0.f;
-        for (int b = 0; b < B; ++b) sum += s_g[b * VT + tid];
+        for (int k = 0; k < B; ++k) {
+            const float g = s_g[at(k, tid)];
+            if (COMPACT && g == 0.f) break;
+            sum += g;
+        }
         db[v0 + tid] = sum;
     }
     if (!dW) return;
@@ -406,21 +441,21 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
             float acc[N];
 #pragma unroll
             for (int i = 0; i < N; ++i) acc[i] = 0.f;
-            for (int b0 = 0; b0 < B; b0 += 8) {
+            for (int k0 = 0; k0 < B; k0 += 8) {
                 float g[8];
                 uint4 x[8];
+                bool open = true;                                // false behind the closing zero
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int b = b0 + u;
-                    g[u] = b < B ? s_g[b * VT + vv] : 0.f;
+                    const int k = k0 + u;
+                    g[u] = (open && k < B) ? s_g[at(k, vv)] : 0.f;
+                    if (COMPACT) open = g[u] != 0.f;
                     x[u] = make_uint4(0, 0, 0, 0);
-                    if (g[u] != 0.f) {                           // only lanes with a contribution fetch
-                        const int idx = s_i[b * VT + vv];
-                        x[u] = *reinterpret_cast<const uint4*>(H + ((size_t)b * S + idx) * D + col0);
-                    }
+                    if (g[u] != 0.f) x[u] = *reinterpret_cast<const uint4*>(H + (size_t)s_i[at(k, vv)] * D + col0);
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) RowChunk<T>::fma(x[u], g[u], acc);
+                if (COMPACT && !open) break;
             }
             if (v < V) {
                 float* out = dW + (size_t)v * D + col0;

@@ -395,14 +395,13 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     }
     if (dW || db) {
         prof.begin(4);
-        // column-sliced gathers (L2-resident slices of H) need D % 64 == 0 and pay off while the (g, I)
-        // staging tile (at most 48 KiB) is at least 32 vocabulary rows wide, i.e. B <= 192: four waves
-        // per workgroup and enough workgroups per CU to hide the gather latency.  Larger batches of
-        // (then usually short) sequences keep the whole-row kernel, which compacts zero gradients.
+        // column-sliced gathers (L2-resident slices of H) need D % 64 == 0 and a (g, I) staging tile (at
+        // most 48 KiB) at least 16 vocabulary rows wide, i.e. B <= 384.  Larger batches keep the
+        // whole-row kernel, which also skips zero gradients.
         int VT = 64;
         while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
         const int vpg = s.dtype == LSR_F32 ? 4 : 8;
-        if (s.D % DWS_COLS == 0 && VT >= 32) {
+        if (s.D % DWS_COLS == 0 && VT >= 16) {
             int waves = VT / vpg;
             waves = waves < 1 ? 1 : (waves > 4 ? 4 : waves);
             const size_t lds = (size_t)s.B * VT * 8;
@@ -414,12 +413,12 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
             NDC = NDC < 1 ? 1 : (NDC > n_dc ? n_dc : NDC);
             const int n_groups = (n_dc + NDC - 1) / NDC;
             const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
-            if (s.dtype == LSR_F32)
-                hipLaunchKernelGGL((bwd_dw_sliced_kernel<float>), grid, block, lds, st_dw, static_cast<const float*>(H), dY, Y, I,
-                                   dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
-            else
-                hipLaunchKernelGGL((bwd_dw_sliced_kernel<uint16_t>), grid, block, lds, st_dw, static_cast<const uint16_t*>(H), dY,
-                                   Y, I, dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC);
+#define LSR_DW(T, C) hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, C>), grid, block, lds, st_dw, static_cast<const T*>(H), dY, Y, I, \
+                                       dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC)
+            // tiles of 16 rows (B > 192) compact their columns to the non-zero gradients first
+            if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
+            else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
+#undef LSR_DW
         } else {
             // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows
             VT = VT > 32 ? 32 : VT;
