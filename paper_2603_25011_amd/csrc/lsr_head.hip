@@ -368,21 +368,27 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
                                    s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
                 bounds = cb;
             }
-            // A wave gathers 32 entries of one bucket per step, or 16 entries of each of two buckets.
-            // Two pay off when a bucket holds too few entries per chunk to keep a wave busy for several
-            // steps (measured: C5, about 90 entries, 3.4 -> 2.8 ms; C4, about 170, the other way round).
+            // A wave gathers 32 entries of one bucket per step, or 32/k entries of each of k buckets.
+            // Several buckets pay off when a bucket holds too few entries per chunk to keep a wave busy
+            // for several steps.  Measured optima (entries per bucket and chunk as estimated here -> k):
+            // 170 -> 1, 85 -> 2, 43 and 21 -> 4, 5 -> 8 (B=128, S=8192: 4.06 ms with k=1, 1.46 with 8).
             // Lengths are not known on the host: sequences are taken to fill 70 % of S and every
             // (b, v) pair to carry a gradient.
             const double per_bucket = (double)s.V / ((0.7 * s.S > 1.0 ? 0.7 * s.S : 1.0) * w.n_vc);
-            const int bpw = (w.n_vc > 1 && per_bucket < 128.0) ? 2 : 1;
+            int bpw = per_bucket >= 128.0 ? 1 : (per_bucket >= 48.0 ? 2 : (per_bucket >= 12.0 ? 4 : 8));
+            if (s.dtype == LSR_F32 && bpw > 4) bpw = 4;      // a float row piece takes 16 lanes
             const int n_groups = s.B * ((s.S + 4 * bpw - 1) / (4 * bpw));
             if ((long long)n_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
             const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
             for (int vc = 0; vc < w.n_vc; ++vc) {
 #define LSR_DH(T, BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW>), grid, dim3(256), 0, st, static_cast<const T*>(W), bounds, \
                                           perm, dH, s.B, s.S, s.D, s.V, n_groups, w.n_vc, vc)
-                if (s.dtype == LSR_F32) { if (bpw == 1) LSR_DH(float, 1); else LSR_DH(float, 2); }
-                else { if (bpw == 1) LSR_DH(uint16_t, 1); else LSR_DH(uint16_t, 2); }
+                if (s.dtype == LSR_F32) {
+                    if (bpw == 1) LSR_DH(float, 1); else if (bpw == 2) LSR_DH(float, 2); else LSR_DH(float, 4);
+                } else {
+                    if (bpw == 1) LSR_DH(uint16_t, 1); else if (bpw == 2) LSR_DH(uint16_t, 2);
+                    else if (bpw == 4) LSR_DH(uint16_t, 4); else LSR_DH(uint16_t, 8);
+                }
 #undef LSR_DH
             }
         } else {

@@ -72,6 +72,8 @@ def test_fp32_small_shapes():
     print(run_case(wl.make_custom(3, 20, 72, 333, dtype="f32", seed=5, w_std=0.05)))
     # D a multiple of 64 and a vocabulary of three dH chunks
     print(run_case(wl.make_custom(3, 20, 64, 40000, dtype="f32", seed=6, w_std=0.05)))
+    # two buckets per wave in the dH gather (about 70 entries per bucket expected)
+    print(run_case(wl.make_custom(3, 20, 64, 1000, dtype="f32", seed=8, w_std=0.05)))
     # a batch above 192: dW from 16-row tiles whose columns are compacted to the non-zero gradients
     print(run_case(wl.make_custom(200, 6, 64, 100, dtype="f32", seed=7, w_std=0.05)))
 
