@@ -45,14 +45,18 @@ __global__ __launch_bounds__(PREP_THREADS) void fwd_prep_kernel(const uint8_t* _
 // Packing plan for the MFMA forward.  Every sequence takes ceil(len / 32) blocks of 32 rows (one
 // block if it has no valid token, so that its zero output is still written); blk0 is the exclusive
 // prefix sum of the block counts, and the block list is cut into n_groups contiguous ranges of whole
-// sequences with about equal block counts: group g starts at the first sequence whose first block
-// is not below g * total / n_groups.  One workgroup; B and n_groups are small next to the GEMM.
+// sequences with about equal block counts, the cuts nudged so that groups hold whole 8-block tiles
+// where a sequence start allows it.  One workgroup; B and n_groups (at most PLAN_MAX_GROUPS) are small
+// next to the GEMM.
 constexpr int PLAN_THREADS = 256;
+constexpr int PLAN_CAND = 5;            // sequence starts proposed per boundary: the even cut and two either side
+constexpr int PLAN_MAX_GROUPS = 1024;
 
 __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __restrict__ len, int* blk0,
                                                                  int* __restrict__ grp_blk0, int B,
-                                                                 int n_groups) {
+                                                                 int n_groups, int nudge) {
     __shared__ int s_scan[PLAN_THREADS];
+    __shared__ int s_cand[(PLAN_MAX_GROUPS + 1) * PLAN_CAND];
     const int tid = threadIdx.x;
     int base = 0;
     for (int b0 = 0; b0 < B; b0 += PLAN_THREADS) {
@@ -80,15 +84,53 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
     __threadfence();
     __syncthreads();
     const int total = base;
+    auto blk0_at = [&](int b) { return __hip_atomic_load(&blk0[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    // Every thread proposes, for its boundaries, the sequence starts around the even cut
+    // g * total / n_groups; one thread then walks the boundaries in order and takes, among the
+    // proposals within half a group of the even cut, the one that leaves the fewest empty block slots
+    // in the last 8-block tile of the group it closes (ties: nearest to the even cut).  A group whose
+    // block count is a multiple of 8 has no ragged tile; a ragged tile pays the whole vocabulary-tile
+    // side of a tile (loads of W, its fragments, barriers, epilogue) for a fraction of the rows.
+    // The nudged groups are less even in size, so the host asks for them (`nudge`) only when the grid
+    // is many workgroups per CU deep.
     for (int g = tid; g <= n_groups; g += PLAN_THREADS) {
         const int target = (int)(((long long)g * total) / n_groups);
         int lo = 0, hi = B;                       // smallest b in [0, B] with blk0[b] >= target
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            const int x = __hip_atomic_load(&blk0[mid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (x >= target) hi = mid; else lo = mid + 1;
+            if (blk0_at(mid) >= target) hi = mid; else lo = mid + 1;
         }
-        grp_blk0[g] = g == n_groups ? total : __hip_atomic_load(&blk0[lo], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!nudge) {                             // even cuts: no boundary depends on another
+            grp_blk0[g] = g == n_groups ? total : blk0_at(lo);
+            continue;
+        }
+#pragma unroll
+        for (int k = 0; k < PLAN_CAND; ++k) {
+            const int c = lo + k - PLAN_CAND / 2;
+            s_cand[g * PLAN_CAND + k] = (c >= 0 && c <= B) ? blk0_at(c) : -1;
+        }
+    }
+    __syncthreads();
+    if (nudge && tid == 0) {
+        const int half = total / (2 * n_groups);
+        int prev = 0;
+        grp_blk0[0] = 0;
+        for (int g = 1; g < n_groups; ++g) {
+            const int target = (int)(((long long)g * total) / n_groups);
+            int best = -1, best_waste = 0, best_dist = 0;
+            for (int k = 0; k < PLAN_CAND; ++k) {
+                const int x = s_cand[g * PLAN_CAND + k];
+                const int dist = x > target ? x - target : target - x;
+                if (x <= prev || (dist > half && k != PLAN_CAND / 2)) continue;
+                const int waste = (8 - ((x - prev) & 7)) & 7;
+                if (best < 0 || waste < best_waste || (waste == best_waste && dist < best_dist)) {
+                    best = x; best_waste = waste; best_dist = dist;
+                }
+            }
+            prev = best < 0 ? prev : best;        // nothing beyond the last boundary: an empty group
+            grp_blk0[g] = prev;
+        }
+        grp_blk0[n_groups] = total;
     }
 }
 

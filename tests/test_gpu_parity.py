@@ -56,6 +56,7 @@ def test_c1_tiny_fp32_forward_backward():
     (40, 260, 128, 300, 100),   # several row groups of several tiles each
     (1, 8, 8, 1, 1),            # smallest legal D, one vocabulary entry
     (2, 16, 128, 70000, 1),     # vocabulary wide enough that the dH gather runs in three vocabulary chunks
+    (48, 200, 64, 70000, 1),    # enough workgroups per CU that the row-group cuts are nudged to whole tiles
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
