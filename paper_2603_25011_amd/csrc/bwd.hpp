@@ -83,11 +83,18 @@ __global__ __launch_bounds__(256) void bwd_scan_kernel(int* __restrict__ cnt, in
     const int b = blockIdx.x, tid = threadIdx.x;
     for (int s = tid; s < S; s += 256) {
         int run = 0;
-        for (int seg = 0; seg < n_seg; ++seg) {
-            const size_t idx = ((size_t)b * n_seg + seg) * S + s;
-            const int c = cnt[idx];
-            cnt[idx] = run;
-            run += c;
+        // eight segments at a time: the loads of a batch are all issued before the first store,
+        // which the compiler cannot do by itself (loads and stores go to the same array)
+        for (int seg0 = 0; seg0 < n_seg; seg0 += 8) {
+            int c[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                c[u] = seg0 + u < n_seg ? cnt[((size_t)b * n_seg + seg0 + u) * S + s] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (seg0 + u < n_seg) cnt[((size_t)b * n_seg + seg0 + u) * S + s] = run;
+                run += c[u];
+            }
         }
         s_tot[s] = run;
     }
@@ -166,6 +173,121 @@ __global__ __launch_bounds__(64) void bwd_place_kernel(const float* __restrict__
         __builtin_amdgcn_wave_barrier();
         if (active && rank == group - 1) s_off[key] = dest + 1;
         __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Placement through LDS (S <= PLACE_MAX_S, segments of at most PLACE_MAX_SEG entries).
+// The kernel above stores every (v, g) pair straight to its bucket: the 64 stores of a step go to some
+// fifty buckets, and with thousands of (b, segment) waves in flight every bucket's line leaves L2
+// between two stores to it (measured at C5: 0.48 GB written for 0.13 GB of pairs).  Here a workgroup
+// of four waves first sorts its whole segment by bucket in LDS and then writes it out in sorted order:
+// the pairs a bucket receives from this segment (about a dozen at C5) leave as one contiguous run.
+//   1. per bucket, the pairs of this segment (difference of two rows of the scanned count table) and
+//      their exclusive prefix = first local slot; s_delta = first global slot - first local slot;
+//   2. steps of 256 pairs: ballot ranking inside each wave as above, then the four waves take their
+//      slots one after the other (wave order = ascending v, so the order inside a bucket is kept);
+//   3. local slot k goes to global slot k + s_delta[bucket of k].
+// A staged pair is (v - vbeg) | bucket << 12 and g.   dynamic LDS: 2*S ints + seg_len pairs.
+// ---------------------------------------------------------------------------------------------
+constexpr int PLACE_MAX_S = 1024;
+constexpr int PLACE_MAX_SEG = 4096;
+
+__global__ __launch_bounds__(256) void bwd_place_staged_kernel(const float* __restrict__ dY,
+                                                               const float* __restrict__ Y,
+                                                               const int* __restrict__ I,
+                                                               const int* __restrict__ cnt,
+                                                               const int* __restrict__ bstart,
+                                                               uint2* __restrict__ perm,
+                                                               int S, int V, int n_seg, int seg_len, int key_bits) {
+    extern __shared__ int s_place[];
+    int* s_next = s_place;                  // [S] next free local slot of each bucket
+    int* s_delta = s_place + S;             // [S] global slot - local slot
+    uint2* s_stage = reinterpret_cast<uint2*>(s_place + 2 * S);     // [seg_len]
+    __shared__ int s_part[256];
+    const int seg = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int* c0 = cnt + ((size_t)b * n_seg + seg) * S;
+    const int* b0 = bstart + (size_t)b * (S + 1);
+    const bool last_seg = seg + 1 == n_seg;
+
+    // 1. counts of this segment, exclusive prefix over the buckets
+    const int per = (S + 255) / 256;
+    const int lo = min(S, tid * per), hi = min(S, lo + per);
+    int sum = 0;
+    for (int s = lo; s < hi; ++s) {
+        const int earlier = c0[s];
+        const int upto = last_seg ? b0[s + 1] - b0[s] : c0[S + s];      // next segment's row, or the bucket size
+        s_next[s] = upto - earlier;
+        s_delta[s] = b0[s] + earlier;
+        sum += upto - earlier;
+    }
+    s_part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int t = 0; t < 256; ++t) { const int c = s_part[t]; s_part[t] = run; run += c; }
+    }
+    __syncthreads();
+    int run = s_part[tid];
+    for (int s = lo; s < hi; ++s) {
+        const int c = s_next[s];
+        s_next[s] = run;
+        s_delta[s] -= run;
+        run += c;
+    }
+    __shared__ int s_total;
+    if (tid == 255) s_total = run;          // the last thread ends on the pairs of the whole segment
+    __syncthreads();
+
+    // 2. rank and stage
+    const int vbeg = seg * seg_len;
+    const int vend = min(V, vbeg + seg_len);
+    const size_t row = (size_t)b * V;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    float n_dy = 0.f, n_y = 0.f;
+    int n_i = 0;
+    auto request = [&](int base) {
+        const int v = base + tid;
+        const bool ok = v < vend;
+        n_dy = ok ? dY[row + v] : 0.f;
+        n_y = ok ? Y[row + v] : 0.f;
+        n_i = ok ? I[row + v] : 0;
+    };
+    request(vbeg);
+    for (int base = vbeg; base < vend; base += 256) {
+        const int v = base + tid;
+        const float g = gate_grad(n_dy, n_y);      // 0 for threads past the end (dy = 0, y = 0)
+        const int key = clamp_pos(n_i, S);
+        request(base + 256);
+        const bool active = g != 0.f;
+        unsigned long long same = __ballot(active);
+        for (int bit = 0; bit < key_bits; ++bit) {
+            const bool one = (key >> bit) & 1;
+            const unsigned long long bm = __ballot(active && one);
+            same &= one ? bm : ~bm;
+        }
+        const int rank = __popcll(same & lt);
+        const int group = __popcll(same);
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+                int slot = 0;
+                if (active) {
+                    slot = s_next[key] + rank;
+                    s_stage[slot] = make_uint2((unsigned)(v - vbeg) | ((unsigned)key << 12), __float_as_uint(g));
+                }
+                __builtin_amdgcn_wave_barrier();     // LDS operations of one wave execute in program order
+                if (active && rank == group - 1) s_next[key] = slot + 1;
+            }
+            __syncthreads();
+        }
+    }
+
+    // 3. sorted write-out
+    const int total = s_total;
+    for (int k = tid; k < total; k += 256) {
+        const uint2 e = s_stage[k];
+        const int key = (int)(e.x >> 12);
+        perm[row + k + s_delta[key]] = make_uint2((unsigned)vbeg + (e.x & 4095u), e.y);
     }
 }
 

@@ -96,6 +96,11 @@ BwdWs bwd_ws(const Shape& s) {
     // table no larger than B*V ints
     long n = 4096 / s.B;
     n = n < s.V / 512 ? n : s.V / 512;
+    // short enough segments for the placement that sorts a segment in LDS, where it applies
+    if (s.S <= PLACE_MAX_S) {
+        const long fit = (s.V + PLACE_MAX_SEG - 129) / (PLACE_MAX_SEG - 128);
+        n = n > fit ? n : fit;
+    }
     n = n < s.V / s.S ? n : s.V / s.S;
     if (n < 1) n = 1;
     w.n_seg = (int)n;
@@ -357,8 +362,12 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
         prof.end(1);
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(2);
-        hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
-                           s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+        if (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG)
+            hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
+                               dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+        else
+            hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
+                               s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
         prof.end(2);
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(3);
