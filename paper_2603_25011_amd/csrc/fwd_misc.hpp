@@ -57,6 +57,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
                                                                  int n_groups, int nudge) {
     __shared__ int s_scan[PLAN_THREADS];
     __shared__ int s_cand[(PLAN_MAX_GROUPS + 1) * PLAN_CAND];
+    __shared__ int s_cut[PLAN_MAX_GROUPS + 1];          // even cuts, then the chosen boundaries
     const int tid = threadIdx.x;
     int base = 0;
     for (int b0 = 0; b0 < B; b0 += PLAN_THREADS) {
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
             grp_blk0[g] = g == n_groups ? total : blk0_at(lo);
             continue;
         }
+        s_cut[g] = target;
 #pragma unroll
         for (int k = 0; k < PLAN_CAND; ++k) {
             const int c = lo + k - PLAN_CAND / 2;
@@ -114,9 +116,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
     if (nudge && tid == 0) {
         const int half = total / (2 * n_groups);
         int prev = 0;
-        grp_blk0[0] = 0;
         for (int g = 1; g < n_groups; ++g) {
-            const int target = (int)(((long long)g * total) / n_groups);
+            const int target = s_cut[g];
             int best = -1, best_waste = 0, best_dist = 0;
             for (int k = 0; k < PLAN_CAND; ++k) {
                 const int x = s_cand[g * PLAN_CAND + k];
@@ -128,10 +129,14 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
                 }
             }
             prev = best < 0 ? prev : best;        // nothing beyond the last boundary: an empty group
-            grp_blk0[g] = prev;
+            s_cut[g] = prev;
         }
-        grp_blk0[n_groups] = total;
+        s_cut[0] = 0;
+        s_cut[n_groups] = total;
     }
+    __syncthreads();
+    if (nudge)
+        for (int g = tid; g <= n_groups; g += PLAN_THREADS) grp_blk0[g] = s_cut[g];
 }
 
 // Row table of the packed layout, one workgroup per sequence: packed row k of the sequence reads
