@@ -56,7 +56,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
                                                                  int* __restrict__ grp_blk0, int B,
                                                                  int n_groups, int nudge) {
     __shared__ int s_scan[PLAN_THREADS];
-    __shared__ int s_cand[(PLAN_MAX_GROUPS + 1) * PLAN_CAND];
+    __shared__ __attribute__((aligned(16))) int s_cand[(PLAN_MAX_GROUPS + 1) * 8];    // PLAN_CAND used of 8 per boundary
     __shared__ int s_cut[PLAN_MAX_GROUPS + 1];          // even cuts, then the chosen boundaries
     const int tid = threadIdx.x;
     int base = 0;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
 #pragma unroll
         for (int k = 0; k < PLAN_CAND; ++k) {
             const int c = lo + k - PLAN_CAND / 2;
-            s_cand[g * PLAN_CAND + k] = (c >= 0 && c <= B) ? blk0_at(c) : -1;
+            s_cand[g * 8 + k] = (c >= 0 && c <= B) ? blk0_at(c) : -1;
         }
     }
     __syncthreads();
@@ -118,15 +118,21 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
         int prev = 0;
         for (int g = 1; g < n_groups; ++g) {
             const int target = s_cut[g];
-            int best = -1, best_waste = 0, best_dist = 0;
+            // the proposals of this boundary in two 16-byte reads, then branch-free selection
+            const int4 c03 = *reinterpret_cast<const int4*>(&s_cand[g * 8]);
+            const int c4 = s_cand[g * 8 + 4];
+            const int cand[PLAN_CAND] = {c03.x, c03.y, c03.z, c03.w, c4};
+            int best = -1, best_key = 0x7fffffff;
+#pragma unroll
             for (int k = 0; k < PLAN_CAND; ++k) {
-                const int x = s_cand[g * PLAN_CAND + k];
+                const int x = cand[k];
                 const int dist = x > target ? x - target : target - x;
-                if (x <= prev || (dist > half && k != PLAN_CAND / 2)) continue;
+                const bool ok = x > prev && (dist <= half || k == PLAN_CAND / 2);
                 const int waste = (8 - ((x - prev) & 7)) & 7;
-                if (best < 0 || waste < best_waste || (waste == best_waste && dist < best_dist)) {
-                    best = x; best_waste = waste; best_dist = dist;
-                }
+                const int key = ok ? (waste << 27) | (dist < (1 << 27) ? dist : (1 << 27) - 1) : 0x7fffffff;
+                const bool take = key < best_key;
+                best_key = take ? key : best_key;
+                best = take ? x : best;
             }
             prev = best < 0 ? prev : best;        // nothing beyond the last boundary: an empty group
             s_cut[g] = prev;

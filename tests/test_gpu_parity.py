@@ -57,6 +57,9 @@ def test_c1_tiny_fp32_forward_backward():
     (1, 8, 8, 1, 1),            # smallest legal D, one vocabulary entry
     (2, 16, 128, 70000, 1),     # vocabulary wide enough that the dH gather runs in three vocabulary chunks
     (48, 200, 64, 70000, 1),    # enough workgroups per CU that the row-group cuts are nudged to whole tiles
+    (2, 1024, 64, 300, 900),    # longest sequences whose bucket sort still places through LDS
+    (2, 1100, 64, 300, 900),    # just beyond: direct placement
+    (3, 40, 64, 9000, 1),       # several sort segments per sequence, the last one short
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
