@@ -229,6 +229,15 @@ def main():
             "note": "flops count valid tokens only; the launch time is the forward call "
                     "(three planning kernels, ~13 us, + the fused kernel) from events on the launch stream"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # second denominator: register-only MFMAs on this machine, at the clock it sustains under that load
+    # (five launches of about 20 ms; the last one is timed)
+    from paper_2603_25011_amd import binding as lsr_binding
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    probe = lsr_binding.lsr_mfma_peak_probe(150000, 5, sink)
+    roof["achievable_peak"] = probe
+    roof["frac_of_achievable"] = roof["achieved"] / probe
+    roof["achievable_note"] = ("lsr_mfma_peak_probe: bf16 32x32x16 MFMAs from registers only, two waves per SIMD; "
+                               "context beside the nominal peak, which stays the denominator of frac")
     del head
     torch.cuda.empty_cache()
 

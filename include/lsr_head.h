@@ -117,6 +117,17 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc,
                                void* workspace, size_t workspace_bytes, void* stream,
                                float* kernel_ms);
 
+/*
+ * Measurement aid, not part of the head: what the matrix cores of the current device deliver on
+ * bf16 32x32x16 MFMAs issued from registers alone (no memory traffic), at the clock the part
+ * sustains under that load.  Runs `launches` back-to-back launches of `iters` rounds per wave on
+ * `stream` (two waves per SIMD, four independent accumulator chains each), times the last one with
+ * events, synchronises, and writes dense TFLOP/s to the HOST double *tflops.  `sink` is a DEVICE
+ * pointer to 4 writable bytes (never written in practice; it keeps the arithmetic alive).
+ * iters in [1, 2^24], launches in [1, 64].
+ */
+int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsr_status_string(int status);
 

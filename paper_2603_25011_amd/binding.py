@@ -53,6 +53,8 @@ def load_library():
     lib.lsr_head_backward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lsr_head_forward_profiled.restype = ctypes.c_int
     lib.lsr_head_forward_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp, fp]
+    lib.lsr_mfma_peak_probe.restype = ctypes.c_int
+    lib.lsr_mfma_peak_probe.argtypes = [ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.lsr_head_backward_profiled.restype = ctypes.c_int
     lib.lsr_head_backward_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, fp]
     lib.lsr_status_string.restype = ctypes.c_char_p
@@ -126,6 +128,13 @@ def lsr_head_forward_profiled(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, work
     _check(load_library().lsr_head_forward_profiled(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(bias), _ptr(mask),
                                                     _ptr(Y), _ptr(I), wp, wb, _stream(stream), ms))
     return list(ms)
+
+
+def lsr_mfma_peak_probe(iters, launches, sink, stream=None):
+    """Dense bf16 TFLOP/s of register-only MFMAs on the current device (measurement aid)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().lsr_mfma_peak_probe(int(iters), int(launches), _ptr(sink), ctypes.byref(out), _stream(stream)))
+    return out.value
 
 
 def lsr_head_backward_profiled(B, S, D, V, hw_dtype, H, W, dY, Y, I, dH, dW, db, workspace, stream=None):

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fwd_bf16.hpp"
+
 namespace lsr {
 
 constexpr int PREP_THREADS = 256;
@@ -198,6 +200,41 @@ __global__ __launch_bounds__(F32_THREADS) void fwd_f32_kernel(const float* __res
     const size_t o = (size_t)b * V + v;
     Y[o] = n > 0 ? log1pf(fmaxf(m + bias[v], 0.f)) : 0.f;
     if (ARG) I[o] = arg;
+}
+
+// Register-only matrix-core probe: every wave issues `iters` rounds of four independent
+// 32x32x16 bf16 MFMAs on operands it never reloads, so the time is the matrix pipes' alone at
+// whatever clock the part sustains under that load.  The result is folded into one value per lane
+// that is compared with a number it cannot take, so nothing is stored; `sink` only keeps the
+// arithmetic alive.  Measurement aid: the denominator "what the matrix cores deliver on this box"
+// beside the nominal peak.
+constexpr int PROBE_THREADS = 256;
+constexpr int PROBE_MFMA_PER_ITER = 4;
+
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(int iters, float* sink) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.001f * (float)((lane + i) & 7));
+        b[i] = (__bf16)(0.002f * (float)((lane * 3 + i) & 7));
+    }
+    floatx16 acc[PROBE_MFMA_PER_ITER];
+#pragma unroll
+    for (int k = 0; k < PROBE_MFMA_PER_ITER; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[k][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < PROBE_MFMA_PER_ITER; ++k)
+            acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < PROBE_MFMA_PER_ITER; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[k][r];
+    if (sum == -1.2345e30f) *sink = sum;      // sums of non-negative products: never taken
 }
 
 }  // namespace lsr

@@ -503,6 +503,36 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc, const void* H, const v
     return rc != LSR_OK ? rc : rc2;
 }
 
+int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, void* stream) {
+    if (!sink || !tflops) return LSR_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24) || launches < 1 || launches > 64) return LSR_ERR_SHAPE;
+    int n_cus = 0;
+    int rc = check_device(&n_cus);
+    if (rc != LSR_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_LAUNCH; }
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return LSR_ERR_LAUNCH; }
+    // two workgroups of four waves per CU: two waves on every SIMD, each with four independent MFMA chains
+    const dim3 grid(2 * n_cus);
+    float ms = 0.f;
+    bool ok = true;
+    for (int l = 0; l < launches && ok; ++l) {        // the last launch is the one that is timed
+        const bool timed = l + 1 == launches;
+        if (timed) ok = hipEventRecord(e0, st) == hipSuccess;
+        hipLaunchKernelGGL(mfma_probe_kernel, grid, dim3(PROBE_THREADS), 0, st, (int)iters, static_cast<float*>(sink));
+        ok = ok && hipGetLastError() == hipSuccess;
+        if (timed) ok = ok && hipEventRecord(e1, st) == hipSuccess;
+    }
+    ok = ok && hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (!ok || ms <= 0.f) { (void)hipGetLastError(); return LSR_ERR_LAUNCH; }
+    const double flops = 2.0 * 32 * 32 * 16 * PROBE_MFMA_PER_ITER * (double)iters * (PROBE_THREADS / 64) * grid.x;
+    *tflops = flops / (ms * 1e-3) / 1e12;
+    return LSR_OK;
+}
+
 const char* lsr_status_string(int status) {
     switch (status) {
         case LSR_OK: return "ok";

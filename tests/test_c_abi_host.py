@@ -30,7 +30,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"lsr_head_forward", "lsr_head_backward", "lsr_head_workspace_bytes", "lsr_status_string",
-            "lsr_head_forward_profiled", "lsr_head_backward_profiled"} <= set(names)
+            "lsr_head_forward_profiled", "lsr_head_backward_profiled", "lsr_mfma_peak_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lsr_head.h but not exported"
 
@@ -109,6 +109,14 @@ def test_profiled_variants_need_a_host_array(lib):
     d = binding._desc(2, 16, 64, 1000, 0)
     rc = lib.lsr_head_forward_profiled(ctypes.byref(d), 4096, 4096, 4096, 4096, 4096, None, 4096, 1 << 30, None, None)
     assert rc == 1
+
+
+def test_probe_argument_errors(lib):
+    out = ctypes.c_double(0.0)
+    assert lib.lsr_mfma_peak_probe(1000, 1, None, ctypes.byref(out), None) == 1
+    assert lib.lsr_mfma_peak_probe(1000, 1, 4096, None, None) == 1
+    assert lib.lsr_mfma_peak_probe(0, 1, 4096, ctypes.byref(out), None) == 2
+    assert lib.lsr_mfma_peak_probe(1000, 65, 4096, ctypes.byref(out), None) == 2
 
 
 def test_without_a_gfx950_device_calls_fail_loudly(lib):

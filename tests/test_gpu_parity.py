@@ -203,3 +203,12 @@ def test_random_shapes_and_masks():
             mask[int(rng.integers(0, B)), :] = 0
         print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep}", flush=True)
         run_case(inp, mask=mask)
+
+
+def test_mfma_probe_reports_a_plausible_rate():
+    from paper_2603_25011_amd import binding as b
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    tf = b.lsr_mfma_peak_probe(20000, 2, sink)
+    print(f"register-only bf16 MFMA rate: {tf:.0f} TFLOP/s")
+    assert 800.0 < tf < 2600.0          # between a third of and just above the nominal 2.5 PFLOP/s
+    assert float(sink.item()) == 0.0    # nothing is ever stored
