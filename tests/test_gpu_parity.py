@@ -205,6 +205,27 @@ def test_random_shapes_and_masks():
         run_case(inp, mask=mask)
 
 
+def test_random_shapes_batched_long_and_wide():
+    """A dozen seeded problems from the corners the first set does not reach: batches of several
+    hundred short sequences (16-row dW tiles, compacted), sequences beyond 1024 positions (direct
+    bucket placement, eight buckets per wave), vocabularies of tens of thousands (chunked dH)."""
+    rng = np.random.default_rng(20260326)
+    for case in range(12):
+        kind = case % 3
+        if kind == 0:
+            B, S, V = int(rng.integers(150, 420)), int(rng.integers(1, 40)), int(rng.integers(1, 2500))
+        elif kind == 1:
+            B, S, V = int(rng.integers(1, 6)), int(rng.integers(300, 1300)), int(rng.integers(1, 1200))
+        else:
+            B, S, V = int(rng.integers(1, 5)), int(rng.integers(1, 60)), int(rng.integers(33000, 90000))
+        D = int(rng.choice([64, 128])) if kind == 2 else int(rng.choice([8, 24, 64, 128, 192, 200, 256, 320]))
+        keep = float(rng.choice([0.02, 0.3, 0.7, 1.0]))
+        inp = wl.make_custom(B, S, D, V, seed=7000 + case)
+        mask = wl.scattered_mask(rng, B, S, keep=keep)
+        print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep}", flush=True)
+        run_case(inp, mask=mask)
+
+
 def test_mfma_probe_reports_a_plausible_rate():
     from paper_2603_25011_amd import binding as b
     sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
