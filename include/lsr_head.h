@@ -20,6 +20,8 @@
  *     forked from and joined back into `stream`, so the caller sees ordinary stream order).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream)
  *     and the call returns without synchronising, except the *_profiled variants.
+ *     Both calls can be recorded into a HIP graph on a capturing stream; make one backward call
+ *     on the device before capturing, so that the auxiliary stream and events already exist.
  *   - Outputs are overwritten; nothing has to be zeroed by the caller.
  *   - All argument checks run on the host before anything is enqueued; on error nothing has
  *     been launched.  The return value is an lsr_status; no exceptions, no abort().
