@@ -585,16 +585,15 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                 for (int c = 0; c < 2; ++c) {
                     // rows grow with the register index, and positions with the rows: the first
                     // register that holds the maximum is the lowest position in this lane
+                    // the maximum by a chain of three-way maxima, then the first register equal to it
                     float m = acc[i][c][0];
-                    int e = 0;
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) {
-                        const float a = acc[i][c][r];
-                        if (ARG) {
-                            if (a > m) { m = a; e = r; }
-                        } else {
-                            m = fmaxf(m, a);
-                        }
+                    for (int r = 1; r < 15; r += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, acc[i][c][r]), acc[i][c][r + 1]);
+                    m = __builtin_fmaxf(m, acc[i][c][15]);
+                    int e = 15;
+                    if (ARG) {
+#pragma unroll
+                        for (int r = 14; r >= 0; --r) e = acc[i][c][r] == m ? r : e;
                     }
                     int s = ARG ? s_rows[buf][acc_row(blk, e, half)].y : 0;
                     const float mo = __shfl_xor(m, 32);
