@@ -595,17 +595,27 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
 #pragma unroll
                         for (int r = 14; r >= 0; --r) e = acc[i][c][r] == m ? r : e;
                     }
-                    int s = ARG ? s_rows[buf][acc_row(blk, e, half)].y : 0;
-                    const float mo = __shfl_xor(m, 32);
-                    const int so = __shfl_xor(s, 32);
-                    if (mo > m || (mo == m && so < s)) { m = mo; s = so; }
                     mm[c] = m;
-                    ss[c] = s;
+                    ss[c] = ARG ? s_rows[buf][acc_row(blk, e, half)].y : 0;
                 }
-                // both half-waves now hold both columns; half h stores column 32 h + l32
+                // Half-wave q stores column 32 q + l32, so it needs the other half-wave's pair for column
+                // block q only.  One swap of the upper half of the c = 0 register with the lower half of
+                // the c = 1 register leaves, in both half-waves, the two candidates of the column the
+                // lane stores (own and partner; which is which does not matter to a symmetric choice).
+                const auto pm = __builtin_amdgcn_permlane32_swap(__float_as_int(mm[0]), __float_as_int(mm[1]), false, false);
+                float m = __int_as_float(pm[0]);
+                const float mo = __int_as_float(pm[1]);
+                int sp = 0;
+                if (ARG) {
+                    const auto ps = __builtin_amdgcn_permlane32_swap(ss[0], ss[1], false, false);
+                    sp = ps[0];
+                    const int so = ps[1];
+                    if (mo > m || (mo == m && so < sp)) sp = so;
+                }
+                m = fmaxf(m, mo);
                 const int col = wn * 64 + half * 32 + l32;
-                s_pm[blk * TN + col] = half ? mm[1] : mm[0];
-                if (ARG) s_ps[blk * TN + col] = half ? ss[1] : ss[0];
+                s_pm[blk * TN + col] = m;
+                if (ARG) s_ps[blk * TN + col] = sp;
             }
         }
         if (nk < NS) wait_vmcnt<0>();     // the next tile's tables, if the slab loop was too short to wait for them
