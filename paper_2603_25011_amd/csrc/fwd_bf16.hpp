@@ -590,13 +590,14 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
 #pragma unroll
                     for (int r = 1; r < 15; r += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, acc[i][c][r]), acc[i][c][r + 1]);
                     m = __builtin_fmaxf(m, acc[i][c][15]);
-                    int e = 15;
+                    // e: row of that register within the block, for half-wave 0 (constants per register)
+                    int e = acc_row(0, 15, 0);
                     if (ARG) {
 #pragma unroll
-                        for (int r = 14; r >= 0; --r) e = acc[i][c][r] == m ? r : e;
+                        for (int r = 14; r >= 0; --r) e = acc[i][c][r] == m ? acc_row(0, r, 0) : e;
                     }
                     mm[c] = m;
-                    ss[c] = ARG ? s_rows[buf][acc_row(blk, e, half)].y : 0;
+                    ss[c] = ARG ? s_rows[buf][blk * FWD_BLK + half * 4 + e].y : 0;
                 }
                 // Half-wave q stores column 32 q + l32, so it needs the other half-wave's pair for column
                 // block q only.  One swap of the upper half of the c = 0 register with the lower half of
