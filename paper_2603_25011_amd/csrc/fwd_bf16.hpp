@@ -625,13 +625,24 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
         // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
         //      the first TN threads take part; without PMRING the others go on to the next tile. ----
         if (tid < TN) {
-            for (int k = 0; k < nact; ++k) {
-                const float m = s_pm[k * TN + tid];
-                if (m > run_m) {                  // later blocks hold higher positions: strict
-                    run_m = m;
-                    if (ARG) run_s = s_ps[k * TN + tid];
+            // all table reads first (the accumulators are dead here, registers are free): the walk over
+            // the blocks is a dependent chain, and the other four waves wait for it at the next barrier
+            float pm[FWD_TB];
+            int ps[FWD_TB], mt[FWD_TB];
+#pragma unroll
+            for (int k = 0; k < FWD_TB; ++k) {
+                const bool live = k < nact;
+                pm[k] = live ? s_pm[k * TN + tid] : -INFINITY;
+                ps[k] = (ARG && live) ? s_ps[k * TN + tid] : 0;
+                mt[k] = live ? s_meta[t & 3][k] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < FWD_TB; ++k) {
+                if (pm[k] > run_m) {              // later blocks hold higher positions: strict
+                    run_m = pm[k];
+                    run_s = ps[k];
                 }
-                const int meta = s_meta[t & 3][k];
+                const int meta = mt[k];
                 if (meta & FWD_META_LAST) {
                     if (v_out < p.V) {
                         const int b = meta & (FWD_META_EMPTY - 1);
