@@ -130,6 +130,18 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc,
  */
 int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, void* stream);
 
+/*
+ * The launch plan the host derives from a shape alone, for inspection and tests (no device needed,
+ * nothing is launched).  Writes LSR_PLAN_SLOTS int32 values to the HOST array `plan`:
+ *   [0] row groups of the packed forward          [1] segments of the bucket sort per sequence
+ *   [2] vocabulary entries per sort segment       [3] 1 if the sort places through LDS, else 0
+ *   [4] vocabulary chunks of the dH gather        [5] vocabulary entries per chunk
+ *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
+ *   [7] rows of the sliced dW gather's staging tile (0: whole-row dW kernel)
+ */
+#define LSR_PLAN_SLOTS 8
+int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsr_status_string(int status);
 

@@ -53,6 +53,8 @@ def load_library():
     lib.lsr_head_backward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lsr_head_forward_profiled.restype = ctypes.c_int
     lib.lsr_head_forward_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp, fp]
+    lib.lsr_head_plan.restype = ctypes.c_int
+    lib.lsr_head_plan.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)]
     lib.lsr_mfma_peak_probe.restype = ctypes.c_int
     lib.lsr_mfma_peak_probe.argtypes = [ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.lsr_head_backward_profiled.restype = ctypes.c_int
@@ -128,6 +130,18 @@ def lsr_head_forward_profiled(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, work
     _check(load_library().lsr_head_forward_profiled(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(bias), _ptr(mask),
                                                     _ptr(Y), _ptr(I), wp, wb, _stream(stream), ms))
     return list(ms)
+
+
+LSR_PLAN_FIELDS = ("fwd_row_groups", "sort_segments", "sort_segment_len", "sort_places_through_lds",
+                   "dh_chunks", "dh_chunk_len", "dh_buckets_per_wave", "dw_tile_rows")
+
+
+def lsr_head_plan(B, S, D, V, hw_dtype):
+    """The host's launch plan for a shape, as a dict (no device needed)."""
+    d = _desc(B, S, D, V, hw_dtype)
+    out = (ctypes.c_int32 * len(LSR_PLAN_FIELDS))()
+    _check(load_library().lsr_head_plan(ctypes.byref(d), out))
+    return dict(zip(LSR_PLAN_FIELDS, (int(x) for x in out)))
 
 
 def lsr_mfma_peak_probe(iters, launches, sink, stream=None):

@@ -118,6 +118,27 @@ BwdWs bwd_ws(const Shape& s) {
     return w;
 }
 
+// Buckets a wave of the sliced dH gather serves.  A wave gathers 32 entries of one bucket per step, or
+// 32/k entries of each of k buckets.  Several buckets pay off when a bucket holds too few entries per
+// chunk to keep a wave busy for several steps.  Measured optima (entries per bucket and chunk as
+// estimated here -> k): 170 -> 1, 85 -> 2, 43 and 21 -> 4, 5 -> 8 (B=128, S=8192: 4.06 ms with k=1,
+// 1.46 with 8).  Lengths are not known on the host: sequences are taken to fill 70 % of S and every
+// (b, v) pair to carry a gradient.
+int dh_buckets_per_wave(const Shape& s, int n_vc) {
+    const double per_bucket = (double)s.V / ((0.7 * s.S > 1.0 ? 0.7 * s.S : 1.0) * n_vc);
+    int bpw = per_bucket >= 128.0 ? 1 : (per_bucket >= 48.0 ? 2 : (per_bucket >= 12.0 ? 4 : 8));
+    if (s.dtype == LSR_F32 && bpw > 4) bpw = 4;      // a float row piece takes 16 lanes
+    return bpw;
+}
+
+// Vocabulary rows of the (g, I) staging tile of the sliced dW gather (at most 48 KiB of LDS), or 0 when
+// the whole-row kernel runs instead (D not a multiple of 64, or a batch too large for 16 rows).
+int dw_tile_rows(const Shape& s) {
+    int VT = 64;
+    while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
+    return (s.D % DWS_COLS == 0 && VT >= 16) ? VT : 0;
+}
+
 int check_device(int* n_cus) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
@@ -362,7 +383,7 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
         prof.end(1);
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(2);
-        if (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG)
+        if (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG)      // plan[3] of lsr_head_plan
             hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
                                dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
         else
@@ -381,15 +402,7 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
                                    s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
                 bounds = cb;
             }
-            // A wave gathers 32 entries of one bucket per step, or 32/k entries of each of k buckets.
-            // Several buckets pay off when a bucket holds too few entries per chunk to keep a wave busy
-            // for several steps.  Measured optima (entries per bucket and chunk as estimated here -> k):
-            // 170 -> 1, 85 -> 2, 43 and 21 -> 4, 5 -> 8 (B=128, S=8192: 4.06 ms with k=1, 1.46 with 8).
-            // Lengths are not known on the host: sequences are taken to fill 70 % of S and every
-            // (b, v) pair to carry a gradient.
-            const double per_bucket = (double)s.V / ((0.7 * s.S > 1.0 ? 0.7 * s.S : 1.0) * w.n_vc);
-            int bpw = per_bucket >= 128.0 ? 1 : (per_bucket >= 48.0 ? 2 : (per_bucket >= 12.0 ? 4 : 8));
-            if (s.dtype == LSR_F32 && bpw > 4) bpw = 4;      // a float row piece takes 16 lanes
+            const int bpw = dh_buckets_per_wave(s, w.n_vc);
             const int n_groups = s.B * ((s.S + 4 * bpw - 1) / (4 * bpw));
             if ((long long)n_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
             const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
@@ -417,9 +430,8 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
         // column-sliced gathers (L2-resident slices of H) need D % 64 == 0 and a (g, I) staging tile (at
         // most 48 KiB) at least 16 vocabulary rows wide, i.e. B <= 384.  Larger batches keep the
         // whole-row kernel, which also skips zero gradients.
-        int VT = 64;
-        while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
-        if (s.D % DWS_COLS == 0 && VT >= 16) {
+        int VT = dw_tile_rows(s);
+        if (VT > 0) {
             // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
             // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
             const int waves = 4;
@@ -439,8 +451,9 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
             else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
 #undef LSR_DW
         } else {
-            // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows
-            VT = VT > 32 ? 32 : VT;
+            // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
+            VT = 32;
+            while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
             const size_t lds = (size_t)s.B * VT * 8;
             const dim3 grid((s.V + VT - 1) / VT);
             if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st_dw, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
@@ -530,6 +543,23 @@ int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops,
     if (!ok || ms <= 0.f) { (void)hipGetLastError(); return LSR_ERR_LAUNCH; }
     const double flops = 2.0 * 32 * 32 * 16 * PROBE_MFMA_PER_ITER * (double)iters * (PROBE_THREADS / 64) * grid.x;
     *tflops = flops / (ms * 1e-3) / 1e12;
+    return LSR_OK;
+}
+
+int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
+    Shape s;
+    const int rc = check_desc(desc, &s);
+    if (rc != LSR_OK) return rc;
+    if (!plan) return LSR_ERR_NULL;
+    const BwdWs w = bwd_ws(s);
+    plan[0] = fwd_row_groups(s);
+    plan[1] = w.n_seg;
+    plan[2] = w.seg_len;
+    plan[3] = (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG) ? 1 : 0;
+    plan[4] = w.n_vc;
+    plan[5] = w.vc_len;
+    plan[6] = s.D % DWS_COLS == 0 ? dh_buckets_per_wave(s, w.n_vc) : 0;
+    plan[7] = dw_tile_rows(s);
     return LSR_OK;
 }
 

@@ -1,0 +1,78 @@
+"""The launch plan the host derives from a shape (lsr_head_plan): documented values for the benchmark
+shapes and the invariants the kernels rely on, over a few thousand random shapes.  No GPU needed."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import paper_2603_25011_amd as lsr
+from paper_2603_25011_amd import binding
+
+
+@pytest.fixture(scope="module", autouse=True)
+def lib():
+    import os
+    if not os.path.exists(lsr.library_path()):
+        from paper_2603_25011_amd import build
+        build.build()
+    return lsr.load_library()
+
+
+def test_plans_of_the_benchmark_shapes():
+    p = lsr.lsr_head_plan(64, 512, 1024, 250002, lsr.LSR_BF16)          # C5
+    assert p == {"fwd_row_groups": 22, "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
+                 "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64}
+    p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
+    assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
+    p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
+    assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"], p["fwd_row_groups"]) == (1, 1, 16, 8)
+    p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
+    assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
+    p = lsr.lsr_head_plan(3, 40, 200, 900, lsr.LSR_BF16)                # D not a multiple of 64: whole-row kernels
+    assert (p["dh_buckets_per_wave"], p["dw_tile_rows"], p["dh_chunks"]) == (0, 0, 1)
+
+
+def test_plan_invariants_on_random_shapes():
+    rng = np.random.default_rng(11)
+    for _ in range(3000):
+        B = int(rng.choice([1, 2, 7, 16, 64, 192, 193, 256, 384, 385, 1000, 6144]))
+        S = int(rng.choice([1, 5, 32, 33, 512, 1024, 1025, 4096, 8192]))
+        D = int(rng.choice([8, 64, 72, 128, 768, 1024, 4096]))
+        V = int(rng.choice([1, 63, 512, 4097, 30522, 32769, 65536, 250002, 1000003]))
+        if B * V >= 2 ** 31 or B * S >= 2 ** 31:
+            continue
+        for dt, esize in ((lsr.LSR_BF16, 2), (lsr.LSR_F32, 4)):
+            p = lsr.lsr_head_plan(B, S, D, V, dt)
+            n_seg, seg_len = p["sort_segments"], p["sort_segment_len"]
+            assert n_seg >= 1 and seg_len % 64 == 0 and n_seg * seg_len >= V and (n_seg - 1) * seg_len < V
+            assert n_seg == 1 or n_seg * S <= V + S              # count table stays within about B*V ints
+            if S <= 1024:
+                assert seg_len <= 4096 and p["sort_places_through_lds"] == 1
+            else:
+                assert p["sort_places_through_lds"] == 0
+            c, clen = p["dh_chunks"], p["dh_chunk_len"]
+            assert 1 <= c <= 64 and c * clen >= V and (c - 1) * clen < V
+            if D % 64 != 0:
+                assert c == 1 and p["dh_buckets_per_wave"] == 0 and p["dw_tile_rows"] == 0
+            else:
+                assert p["dh_buckets_per_wave"] in ((1, 2, 4) if dt == lsr.LSR_F32 else (1, 2, 4, 8))
+                assert c == 1 or c <= V * esize // (32 * S)      # re-reading dH stays below a quarter of the gathers
+                assert c == 1 or clen * 64 * esize <= (4 << 20) or c == 64 or c == V * esize // (32 * S)
+                rows = p["dw_tile_rows"]
+                assert rows in (0, 16, 32, 64) and B * rows * 8 <= 48 * 1024
+                assert (rows == 0) == (B * 16 * 8 > 48 * 1024)
+            assert 1 <= p["fwd_row_groups"] <= min(B, 1024)
+            # the backward workspace holds what the plan implies
+            need = 8 * B * V + 4 * B * n_seg * S + 4 * B * (S + 1) + (4 * B * S * (c + 1) if c > 1 else 0)
+            if S <= 8192 and B <= 6144:
+                ws = lsr.lsr_head_workspace_bytes(B, S, D, V, dt, True)
+                assert need <= ws <= need + 4 * 256
+
+
+def test_plan_argument_errors(lib):
+    out = (ctypes.c_int32 * 8)()
+    d = binding._desc(2, 16, 64, 1000, lsr.LSR_BF16)
+    assert lib.lsr_head_plan(ctypes.byref(d), None) == 1
+    bad = binding._desc(2, 16, 60, 1000, lsr.LSR_BF16)
+    assert lib.lsr_head_plan(ctypes.byref(bad), out) == 2
+    assert lib.lsr_head_plan(None, out) == 1
