@@ -138,8 +138,9 @@ int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops,
  *   [4] vocabulary chunks of the dH gather        [5] vocabulary entries per chunk
  *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
  *   [7] rows of the sliced dW gather's staging tile (0: whole-row dW kernel)
+ *   [8] sequences per launch of the sliced dW gather (B: one launch)
  */
-#define LSR_PLAN_SLOTS 8
+#define LSR_PLAN_SLOTS 9
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
 
 /* Static, NUL-terminated description of a status code. */

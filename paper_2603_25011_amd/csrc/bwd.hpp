@@ -469,6 +469,9 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // b*VT + (vv ^ (b % VT)), so that staging (lanes along vv), compaction (lanes along b) and the gather
 // (eight columns per wave) all spread over the LDS banks.  Without it the tile is plain row-major
 // and every b is visited (measured 7 % faster on dense gradients).   VT a power of two.
+// When the H slice of the whole batch (B*S rows x 128 bytes) is larger than L2, the host launches
+// the kernel once per chunk of consecutive sequences (b_first, B = sequences of the chunk); later
+// launches add to dW and db, which keeps the order of the sums fixed.
 // dynamic LDS: B*VT floats + B*VT ints.   grid = ceil(V/VT) * ceil((D/64)/NDC).
 // ---------------------------------------------------------------------------------------------
 constexpr int DWS_COLS = 64;
@@ -479,7 +482,10 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
                                                             const float* __restrict__ Y,
                                                             const int* __restrict__ I,
                                                             float* __restrict__ dW, float* __restrict__ db,
-                                                            int B, int S, int D, int V, int VT, int n_vtiles, int NDC) {
+                                                            int b_first, int B, int add, int S, int D, int V, int VT,
+                                                            int n_vtiles, int NDC) {
+    // b_first, B: the sequences of this launch (see below); add: dW and db already hold the sums over
+    // the sequences before b_first and are added to
     constexpr int N = RowChunk<T>::N;          // elements per 16-byte chunk
     constexpr int LPR = DWS_COLS / N;          // lanes per row piece
     constexpr int VPG = 64 / LPR;              // vocabulary rows a wave serves at once
@@ -505,7 +511,7 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
             const int e = e0 + u * blockDim.x;
             const int bb = e / VT, vv = e - bb * VT;
             const bool ok = e < B * VT && v0 + vv < V;
-            const size_t o = ok ? (size_t)bb * V + v0 + vv : 0;
+            const size_t o = ok ? (size_t)(b_first + bb) * V + v0 + vv : 0;
             dy[u] = ok ? dY[o] : 0.f;
             y[u] = ok ? Y[o] : 0.f;
             ix[u] = ok ? I[o] : 0;
@@ -516,7 +522,7 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
             if (e < B * VT) {
                 const int bb = e / VT, vv = e - bb * VT;
                 s_g[at(bb, vv)] = gate_grad(dy[u], y[u]);
-                s_i[at(bb, vv)] = bb * S + clamp_pos(ix[u], S);
+                s_i[at(bb, vv)] = (b_first + bb) * S + clamp_pos(ix[u], S);
             }
         }
     }
@@ -545,7 +551,7 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
     if (COMPACT) __syncthreads();
 
     if (db && dg == 0 && tid < VT && v0 + tid < V) {           // fixed-order sum over b
-        float sum = 0.f;
+        float sum = add ? db[v0 + tid] : 0.f;
         for (int k = 0; k < B; ++k) {
             const float g = s_g[at(k, tid)];
             if (COMPACT && g == 0.f) break;
@@ -582,8 +588,14 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
             if (v < V) {
                 float* out = dW + (size_t)v * D + col0;
 #pragma unroll
-                for (int i = 0; i < N; i += 4)
-                    *reinterpret_cast<float4*>(out + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+                for (int i = 0; i < N; i += 4) {
+                    float4 r = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+                    if (add) {
+                        const float4 prev = *reinterpret_cast<const float4*>(out + i);
+                        r = make_float4(prev.x + r.x, prev.y + r.y, prev.z + r.z, prev.w + r.w);
+                    }
+                    *reinterpret_cast<float4*>(out + i) = r;
+                }
             }
         }
     }

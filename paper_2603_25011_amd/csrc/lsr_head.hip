@@ -131,11 +131,32 @@ int dh_buckets_per_wave(const Shape& s, int n_vc) {
     return bpw;
 }
 
-// Vocabulary rows of the (g, I) staging tile of the sliced dW gather (at most 48 KiB of LDS), or 0 when
-// the whole-row kernel runs instead (D not a multiple of 64, or a batch too large for 16 rows).
+// Sequences per launch of the sliced dW gather.  The gather is L2-resident while the H slice of the
+// sequences in flight (rows x 64 columns) is about 4 MB; larger batches are cut into chunks of
+// consecutive sequences, each launch adding to dW (8*|V|*D bytes re-read and re-written per extra
+// launch, capped at a quarter of the gather traffic and at 16 launches).  B=256, S=512, |V|=250002:
+// dW 14.5 ms in one launch of 16-row tiles (16.8 MB slice).
+int dw_batch_chunk(const Shape& s) {
+    const long esize = s.dtype == LSR_F32 ? 4 : 2;
+    const long per_seq = (long)s.S * DWS_COLS * esize;
+    long bc = (4l << 20) / per_seq;
+    bc = bc < 1 ? 1 : bc;
+    long n = (s.B + bc - 1) / bc;
+    const long cap = 1 + (long)s.B * esize / 32;
+    n = n > cap ? cap : n;
+    n = n > 16 ? 16 : n;
+    if ((long)s.V < 16l * s.S) n = 1;      // a row of H is gathered about |V|/S times: too few for L2 to matter
+    n = n < 1 ? 1 : n;
+    return (int)((s.B + n - 1) / n);
+}
+
+// Vocabulary rows of the (g, I) staging tile of the sliced dW gather (at most 48 KiB of LDS for the
+// sequences of one launch), or 0 when the whole-row kernel runs instead (D not a multiple of 64, or
+// too many sequences per launch for 16 rows).
 int dw_tile_rows(const Shape& s) {
+    const int nb = dw_batch_chunk(s);
     int VT = 64;
-    while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
+    while (VT > 1 && (size_t)nb * VT * 8 > 48 * 1024) VT /= 2;
     return (s.D % DWS_COLS == 0 && VT >= 16) ? VT : 0;
 }
 
@@ -435,20 +456,24 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
             // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
             // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
             const int waves = 4;
-            const size_t lds = (size_t)s.B * VT * 8;
+            const int bc = dw_batch_chunk(s);                  // sequences per launch
+            const size_t lds = (size_t)bc * VT * 8;
             const int n_vtiles = (s.V + VT - 1) / VT;
-            // slices per group: about 3 MiB of H rows (B*S rows x 64 columns each) stay L2-resident
+            // slices per group: about 3 MiB of H rows (rows of a launch x 64 columns each) stay L2-resident
             const int n_dc = s.D / DWS_COLS;
-            const size_t slice_bytes = (size_t)s.B * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
+            const size_t slice_bytes = (size_t)bc * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
             int NDC = (int)((size_t)(3u << 20) / slice_bytes);
             NDC = NDC < 1 ? 1 : (NDC > n_dc ? n_dc : NDC);
             const int n_groups = (n_dc + NDC - 1) / NDC;
             const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
 #define LSR_DW(T, C) hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, C>), grid, block, lds, st_dw, static_cast<const T*>(H), dY, Y, I, \
-                                       dW, db, s.B, s.S, s.D, s.V, VT, n_vtiles, NDC)
-            // tiles of 16 rows (B > 192) compact their columns to the non-zero gradients first
-            if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
-            else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
+                                       dW, db, b0, nb, b0 > 0 ? 1 : 0, s.S, s.D, s.V, VT, n_vtiles, NDC)
+            for (int b0 = 0; b0 < s.B; b0 += bc) {
+                const int nb = s.B - b0 < bc ? s.B - b0 : bc;
+                // tiles of 16 rows (more than 192 sequences per launch) compact their columns to the non-zero gradients first
+                if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
+                else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
+            }
 #undef LSR_DW
         } else {
             // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
@@ -560,6 +585,7 @@ int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     plan[5] = w.vc_len;
     plan[6] = s.D % DWS_COLS == 0 ? dh_buckets_per_wave(s, w.n_vc) : 0;
     plan[7] = dw_tile_rows(s);
+    plan[8] = dw_batch_chunk(s);
     return LSR_OK;
 }
 

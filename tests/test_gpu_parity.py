@@ -60,6 +60,7 @@ def test_c1_tiny_fp32_forward_backward():
     (2, 1024, 64, 300, 900),    # longest sequences whose bucket sort still places through LDS
     (2, 1100, 64, 300, 900),    # just beyond: direct placement
     (3, 40, 64, 9000, 1),       # several sort segments per sequence, the last one short
+    (260, 256, 64, 4100, 60),   # a batch whose H slice exceeds L2: the dW gather runs in three launches of 87 sequences
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
@@ -78,6 +79,8 @@ def test_fp32_small_shapes():
     print(run_case(wl.make_custom(3, 20, 64, 40000, dtype="f32", seed=6, w_std=0.05)))
     # two buckets per wave in the dH gather (about 70 entries per bucket expected)
     print(run_case(wl.make_custom(3, 20, 64, 1000, dtype="f32", seed=8, w_std=0.05)))
+    # dW in two launches of 100 sequences (the second adds to the first)
+    print(run_case(wl.make_custom(200, 128, 64, 2100, dtype="f32", seed=9, w_std=0.05)))
     # a batch above 192: dW from 16-row tiles whose columns are compacted to the non-zero gradients
     print(run_case(wl.make_custom(200, 6, 64, 100, dtype="f32", seed=7, w_std=0.05)))
 

@@ -21,13 +21,16 @@ def lib():
 def test_plans_of_the_benchmark_shapes():
     p = lsr.lsr_head_plan(64, 512, 1024, 250002, lsr.LSR_BF16)          # C5
     assert p == {"fwd_row_groups": 22, "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
-                 "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64}
+                 "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64,
+                 "dw_sequences_per_launch": 64}
     p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
     p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"], p["fwd_row_groups"]) == (1, 1, 16, 8)
     p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
     assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
+    p = lsr.lsr_head_plan(256, 512, 768, 250002, lsr.LSR_BF16)          # a batch whose H slice is 4x L2: four dW launches
+    assert (p["dw_sequences_per_launch"], p["dw_tile_rows"]) == (64, 64)
     p = lsr.lsr_head_plan(3, 40, 200, 900, lsr.LSR_BF16)                # D not a multiple of 64: whole-row kernels
     assert (p["dh_buckets_per_wave"], p["dw_tile_rows"], p["dh_chunks"]) == (0, 0, 1)
 
@@ -58,9 +61,12 @@ def test_plan_invariants_on_random_shapes():
                 assert p["dh_buckets_per_wave"] in ((1, 2, 4) if dt == lsr.LSR_F32 else (1, 2, 4, 8))
                 assert c == 1 or c <= V * esize // (32 * S)      # re-reading dH stays below a quarter of the gathers
                 assert c == 1 or clen * 64 * esize <= (4 << 20) or c == 64 or c == V * esize // (32 * S)
-                rows = p["dw_tile_rows"]
-                assert rows in (0, 16, 32, 64) and B * rows * 8 <= 48 * 1024
-                assert (rows == 0) == (B * 16 * 8 > 48 * 1024)
+                rows, nb = p["dw_tile_rows"], p["dw_sequences_per_launch"]
+                assert 1 <= nb <= B and (B + nb - 1) // nb <= 16
+                assert rows in (0, 16, 32, 64) and nb * rows * 8 <= 48 * 1024
+                assert (rows == 0) == (nb * 16 * 8 > 48 * 1024)
+                # several launches only where rows of H are reused often, and few enough that re-reading dW stays small
+                assert nb == B or (V >= 16 * S and (B + nb - 1) // nb <= min(16, 1 + B * esize // 32))
             assert 1 <= p["fwd_row_groups"] <= min(B, 1024)
             # the backward workspace holds what the plan implies
             need = 8 * B * V + 4 * B * n_seg * S + 4 * B * (S + 1) + (4 * B * S * (c + 1) if c > 1 else 0)
@@ -70,7 +76,7 @@ def test_plan_invariants_on_random_shapes():
 
 
 def test_plan_argument_errors(lib):
-    out = (ctypes.c_int32 * 8)()
+    out = (ctypes.c_int32 * 16)()
     d = binding._desc(2, 16, 64, 1000, lsr.LSR_BF16)
     assert lib.lsr_head_plan(ctypes.byref(d), None) == 1
     bad = binding._desc(2, 16, 60, 1000, lsr.LSR_BF16)
