@@ -89,74 +89,23 @@ __device__ __forceinline__ int acc_row(int blk, int r, int half) {
     return blk * FWD_BLK + (r >> 2) * 8 + half * 4 + (r & 3);
 }
 
-// One K slab of MFMAs for the first NA of this wave's four row blocks.  With PF the fragments are
-// double buffered in registers: the reads for k-step ks+1 are issued during the MFMAs of k-step ks,
-// so the LDS latency (longer while direct-to-LDS writes are landing) hides behind them.
-// NDMA direct-to-LDS loads of a later slab are issued from inside the MFMA stream, spread evenly
-// over the first SPREAD k-steps.  A burst of loads right after the barrier makes every wave sit in
-// the vector-memory issue queue (the address unit takes ~16 cycles per 1 KiB wave load) while the
-// MFMA pipe idles; interleaved, the pipe keeps running on the MFMAs already issued.
-template <int NA, int KS, bool PF, int NDMA, int SPREAD, typename DmaFn>
+// One K slab of MFMAs for the first NA of this wave's four row blocks, fragments read per k-step
+// (register-staged loader; the direct-to-LDS pipeline uses mma_rot below).
+template <int NA, int KS>
 __device__ __forceinline__ void mma_slab(const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
-                                         const int (&fsw)[KS], floatx16 (&acc)[4][2], DmaFn&& dma) {
-    constexpr int M = NA * 2;                              // MFMAs per k-step
-    constexpr int Q = SPREAD > 0 ? NDMA / SPREAD : 0;      // loads per k-step while spreading
-    if constexpr (PF) {
-        bf16x8 fa[2][NA], fb[2][2];
+                                         const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) fb[0][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[0]);
+    for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 fa[NA], fb[2];
 #pragma unroll
-        for (int i = 0; i < NA; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[0]);
+        for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks]);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            // Fragment read q of the next k-step, in the order its MFMAs consume them:
-            // B0, A0, B1, A1, A2, ...  One read is issued behind each MFMA of this k-step, not as a
-            // burst: both waves of a SIMD leave the barrier in phase, and while they both sit in a
-            // burst of LDS reads nobody feeds the matrix pipe.
-            auto read_next = [&](int q) {
-                if (ks + 1 < KS && q < NA + 2) {
-                    if (q == 0 || q == 2) {
-                        const int c = q >> 1;
-                        fb[nxt][c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks + 1]);
-                    } else {
-                        const int i = q == 1 ? 0 : q - 2;
-                        fa[nxt][i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks + 1]);
-                    }
-                }
-            };
+        for (int i = 0; i < NA; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks]);
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                acc[m >> 1][m & 1] =
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m >> 1], fb[cur][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
-                read_next(m);
-                if (m == M - 1) {
+        for (int i = 0; i < NA; ++i)
 #pragma unroll
-                    for (int q = M; q < NA + 2; ++q) read_next(q);
-                }
-                if (ks < SPREAD) {
-                    // after MFMA m the number of issued loads is topped up to ceil((m+1) Q / M)
-                    const int lo = (m * Q + M - 1) / M, hi = ((m + 1) * Q + M - 1) / M;
-#pragma unroll
-                    for (int t = lo; t < hi; ++t) dma(ks * Q + t);
-                }
-                __builtin_amdgcn_sched_barrier(0);      // keep this interleaving
-            }
-        }
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 fa[NA], fb[2];
-#pragma unroll
-            for (int c = 0; c < 2; ++c) fb[c] = *reinterpret_cast<const bf16x8*>(sb + c * b_stride + fsw[ks]);
-#pragma unroll
-            for (int i = 0; i < NA; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + i * a_stride + fsw[ks]);
-#pragma unroll
-            for (int i = 0; i < NA; ++i)
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-                    acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
-        }
+            for (int c = 0; c < 2; ++c)
+                acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[c], acc[i][c], 0, 0, 0);
     }
 }
 
@@ -226,18 +175,15 @@ __device__ __forceinline__ void mma_rot(const uint8_t* sa, int a_stride, const u
     }
 }
 
-template <int KS, bool PF, int NDMA, int SPREAD, typename DmaFn>
+template <int KS>
 __device__ __forceinline__ void mma_dispatch(int na, const uint8_t* sa, int a_stride, const uint8_t* sb, int b_stride,
-                                             const int (&fsw)[KS], floatx16 (&acc)[4][2], DmaFn&& dma) {
+                                             const int (&fsw)[KS], floatx16 (&acc)[4][2]) {
     switch (na) {
-        case 4: mma_slab<4, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
-        case 3: mma_slab<3, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
-        case 2: mma_slab<2, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
-        case 1: mma_slab<1, KS, PF, NDMA, SPREAD>(sa, a_stride, sb, b_stride, fsw, acc, dma); break;
-        default:                                    // no live row block in this wave: only its loads
-#pragma unroll
-            for (int n = 0; n < NDMA; ++n) dma(n);
-            break;
+        case 4: mma_slab<4, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 3: mma_slab<3, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 2: mma_slab<2, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        case 1: mma_slab<1, KS>(sa, a_stride, sb, b_stride, fsw, acc); break;
+        default: break;                             // no live row block in this wave
     }
 }
 
@@ -279,16 +225,20 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 
-// NWN   wave columns (4: 8 waves, 256 x 256 tile, one workgroup per CU;
-//                     2: 4 waves, 256 x 128 tile, two workgroups per CU that hide each other's
-//                        barriers, load waits and epilogues)
-// PMRING  the per-block maxima of the epilogue live in a ring stage that is idle by then instead of
-//         in LDS of their own (needed to fit two workgroups of three stages in 160 KB)
-template <int NWN, bool ARG, int BK, int NS, bool DMA, bool PMRING, int SPREAD = BK / 32>
-__global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams p) {
-    static_assert(BK == 64 || BK == 32, "slab depth");
-    static_assert(DMA || (BK == 64 && NS == 2 && NWN == 4), "register-staged loader: BK = 64, two stages, 8 waves");
-    static_assert(!PMRING || (DMA && NS == 3), "epilogue maxima borrow the idle third stage");
+// One workgroup of 8 waves (2 wave rows x 4 wave columns) per CU on a 256 x 256 tile, K in slabs of 64
+// through a ring of two LDS stages.
+//   ARG  track the arg-max position (I requested)
+//   DMA  operands go global -> LDS directly (D a multiple of 64, H and W below 4 GiB each); otherwise
+//        through registers, with 64-bit addresses and a zero-filled last slab
+// (Variants that were built and measured slower - two 4-wave workgroups per CU on 256 x 128 tiles,
+//  32-deep slabs in three or four stages - are described in the design notes, not kept as parameters.)
+constexpr int FWD_NWN = 4;               // wave columns
+template <bool ARG, bool DMA>
+__global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdParams p) {
+    constexpr int NWN = FWD_NWN;
+    constexpr int BK = 64;                   // K elements per slab
+    constexpr int NS = 2;                    // ring stages
+    constexpr int SPREAD = 2;                // k-steps over which the loads of the next slab are spread
     constexpr int NW = 2 * NWN;              // waves
     constexpr int TN = fwd_tn(NWN);
     constexpr int RB = BK * 2;               // bytes per tile row per slab
@@ -303,21 +253,16 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     constexpr int LPT = IPA + IPB;           // loads per thread per slab (A then B)
     constexpr int JSTEP = NW * 1024;         // LDS bytes between a wave's consecutive accesses
     constexpr int PM_BYTES = FWD_TB * TN * 4;
-    static_assert(!PMRING || 2 * PM_BYTES <= STAGE, "maxima and positions must fit one stage");
 
     // One array per ring stage: distinct objects keep the compiler from serialising a fragment read
-    // of one stage against traffic into another.  Stages beyond NS are never referenced and cost nothing.
+    // of one stage against traffic into another.
     __shared__ __attribute__((aligned(1024))) uint8_t s_ring0[STAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t s_ring1[STAGE];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring2[STAGE];
-    __shared__ __attribute__((aligned(1024))) uint8_t s_ring3[STAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t s_pair[2][STAGE];      // register-staged loader only
     auto ring = [&](auto st) -> uint8_t* {
         constexpr int ST = decltype(st)::value;
         if constexpr (ST == 0) return &s_ring0[0];
-        else if constexpr (ST == 1) return &s_ring1[0];
-        else if constexpr (ST == 2) return &s_ring2[0];
-        else return &s_ring3[0];
+        else return &s_ring1[0];
     };
     // Row tables of the current and the next tile (double buffered: the next tile's are fetched,
     // straight into LDS, while this one is multiplied).
@@ -326,7 +271,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
     // when the records of tile t+1 arrive
     __shared__ __attribute__((aligned(64))) int s_meta[4][16];
     // per (block, column): max logit of the block and its position
-    __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[PMRING ? 16 : 2 * PM_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[2 * PM_BYTES];
 
     // ---- workgroup -> (row group, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
@@ -428,7 +373,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
         const bool has_next = t + 1 < n_tiles;
         // With two stages and an even slab count a tile ends in stage 1, so the first slab of the next
         // tile can be requested into stage 0 from inside the last slab and flies during the epilogue.
-        const bool pf_next = DMA && NS == 2 && has_next && nk >= 2 && (nk & 1) == 0;
+        const bool pf_next = DMA && has_next && nk >= 2 && (nk & 1) == 0;
         if (!prefetched) row_offsets(buf);
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(t + 1, buf ^ 1);
@@ -462,7 +407,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
             // made per tile, outside the loop, so that each instance is straight-line MFMA code.
             auto run_slabs = [&](auto na_c) {
                 constexpr int NA = decltype(na_c)::value;
-                static_assert(NS == 2, "the rotated pipeline is written for two stages");
                 bf16x8 fa[2][4], fb[2][2];
                 // One pipeline step: barrier that publishes slab kt (stage ST), then a slab's worth of
                 // MFMAs (see mma_rot) with the loads of slab kt + 1 riding inside them.
@@ -558,22 +502,14 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                 if (kt + 1 < nk) gload(kt + 1);
                 const uint8_t* sa = &s_pair[st][fa_row * RB];
                 const uint8_t* sb = &s_pair[st][SLAB_A + fb_row * RB];
-                mma_dispatch<KS, false, 0, 0>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc, [](int) {});
+                mma_dispatch<KS>(na, sa, A_STRIDE, sb, B_STRIDE, fsw, acc);
                 if (kt + 1 < nk) lstore(st ^ 1);
                 __syncthreads();
             }
         }
 
         // ---- epilogue, part 1: every live block of this wave -> one (max, position) per column ----
-        // With PMRING the table borrows the ring stage that slab nk would use: no load was issued
-        // into it after slab nk - NS landed, and nobody reads it during the last slab.
-        float* s_pm;
-        if constexpr (PMRING) {
-            const int idle = nk % NS;
-            s_pm = reinterpret_cast<float*>(idle == 0 ? &s_ring0[0] : (idle == 1 ? &s_ring1[0] : &s_ring2[0]));
-        } else {
-            s_pm = reinterpret_cast<float*>(&s_pm_own[0]);
-        }
+        float* s_pm = reinterpret_cast<float*>(&s_pm_own[0]);
         int* s_ps = reinterpret_cast<int*>(s_pm) + FWD_TB * TN;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -623,7 +559,7 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
         __syncthreads();
         prefetched = pf_next;
         // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
-        //      the first TN threads take part; without PMRING the others go on to the next tile. ----
+        //      the first TN threads take part; the others go on to the next tile. ----
         if (tid < TN) {
             // all table reads first (the accumulators are dead here, registers are free): the walk over
             // the blocks is a dependent chain, and the other four waves wait for it at the next barrier
@@ -656,7 +592,6 @@ __global__ __launch_bounds__(fwd_threads(NWN), 2) void fwd_bf16_kernel(FwdParams
                 }
             }
         }
-        if constexpr (PMRING) __syncthreads();   // the borrowed stage goes back to the loader
     }
 }
 

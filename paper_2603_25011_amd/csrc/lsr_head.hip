@@ -210,27 +210,24 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : L
 
 // Loader choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab, else the
 // register-staged loader that can zero-fill the last slab.
-// Kernel choice: one 8-wave workgroup per CU on a 256 x 256 tile; the direct-to-LDS ring when D is
-// a multiple of the 64-wide K slab and H and W are each below 4 GiB, else the register-staged loader
-// (64-bit addresses, zero-fills the last slab).  (The kernel also builds as two 4-wave workgroups
-// per CU on 256 x 128 tiles with a ring of three 32-deep stages; that moves 1.5x the bytes into LDS
-// and measured 20 % slower.)
-template <int NWN, int BK, int NS, bool DMA, bool PMRING>
+// Kernel choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab and H and W are
+// each below 4 GiB (32-bit byte offsets per lane), else the register-staged loader (64-bit addresses,
+// zero-fills the last slab).
+template <bool DMA>
 void launch_fwd_cfg(FwdParams p, int V, bool arg, hipStream_t st) {
-    constexpr int TN = fwd_tn(NWN);
+    constexpr int TN = fwd_tn(FWD_NWN);
     p.n_vtiles = (V + TN - 1) / TN;
     p.gv = FWD_GV_COLS / TN;
     p.n_logical = (p.n_vtiles + p.gv - 1) / p.gv * p.gv * p.n_rowgroups;
-    const dim3 grid((p.n_logical + 7) / 8 * 8), block(fwd_threads(NWN));
-    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<NWN, true, BK, NS, DMA, PMRING>), grid, block, 0, st, p);
-    else     hipLaunchKernelGGL((fwd_bf16_kernel<NWN, false, BK, NS, DMA, PMRING>), grid, block, 0, st, p);
+    const dim3 grid((p.n_logical + 7) / 8 * 8), block(fwd_threads(FWD_NWN));
+    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA>), grid, block, 0, st, p);
+    else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA>), grid, block, 0, st, p);
 }
 
 void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
-    // the direct-to-LDS loader addresses operand rows with 32-bit byte offsets
     const bool small = (size_t)p.B * p.S * p.D * 2 < ((size_t)1 << 32) && (size_t)p.V * p.D * 2 < ((size_t)1 << 32);
-    if (p.D % 64 == 0 && small) launch_fwd_cfg<4, 64, 2, true, false>(p, p.V, arg, st);
-    else launch_fwd_cfg<4, 64, 2, false, false>(p, p.V, arg, st);
+    if (p.D % 64 == 0 && small) launch_fwd_cfg<true>(p, p.V, arg, st);
+    else launch_fwd_cfg<false>(p, p.V, arg, st);
 }
 
 int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
