@@ -457,7 +457,7 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // served by the memory-side cache at a fraction of the L2 rate.  Here the work is cut into slices of
 // 64 hidden-state columns and the grid is ordered slice-major: the workgroups resident at any time
 // all gather from the same [tokens x 64] slice of H (a few MB at most), which stays in every XCD's
-// L2 (the host sizes a group of NDC consecutive slices to about 3 MiB of H and a workgroup walks the
+// L2 (the host sizes a group of NDC consecutive slices to at most 9 MiB of H and a workgroup walks the
 // slices of its group, so that the (g, I) staging is not repeated more often than needed).
 // A row piece is 64 elements = LPR lanes x 16 bytes; a wave therefore serves 64/LPR vocabulary
 // rows at once, walks the sequences that have a gradient for them with eight gathers in flight per

@@ -456,10 +456,13 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
             const int bc = dw_batch_chunk(s);                  // sequences per launch
             const size_t lds = (size_t)bc * VT * 8;
             const int n_vtiles = (s.V + VT - 1) / VT;
-            // slices per group: about 3 MiB of H rows (rows of a launch x 64 columns each) stay L2-resident
+            // slices per group: a workgroup walks the slices of its group with one staging of (g, I), and
+            // the groups run one after the other.  Up to 9 MiB of H rows per group measured best (C5: two
+            // 4 MiB slices, dW 2.21 -> 2.02 ms; C3 0.22 -> 0.175; 3 per group at C5 2.11, all 16: 2.48):
+            // fewer stagings against a wider window of H in flight.
             const int n_dc = s.D / DWS_COLS;
             const size_t slice_bytes = (size_t)bc * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
-            int NDC = (int)((size_t)(3u << 20) / slice_bytes);
+            int NDC = (int)((size_t)(9u << 20) / slice_bytes);
             NDC = NDC < 1 ? 1 : (NDC > n_dc ? n_dc : NDC);
             const int n_groups = (n_dc + NDC - 1) / NDC;
             const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
