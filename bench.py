@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE / WRITE_SIZE runs of this same script (summaries: profiles/c5_hbm_counters.txt).
 # FETCH_SIZE is scaled by 2.00 and WRITE_SIZE by 1.00, the factors a 1 GiB copy gives (--calib-copy).
 MEASURED_FWD_TRAFFIC_BYTES = {
-    "c5_large_fwdbwd": int((7364061 * 2.00 + 125789 * 1.00) * 1024),
+    "c5_large_fwdbwd": int((7335657 * 2.00 + 125792 * 1.00) * 1024),
 }
 
 
