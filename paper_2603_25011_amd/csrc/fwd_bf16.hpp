@@ -230,8 +230,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 //   ARG  track the arg-max position (I requested)
 //   DMA  operands go global -> LDS directly (D a multiple of 64, H and W below 4 GiB each); otherwise
 //        through registers, with 64-bit addresses and a zero-filled last slab
-// (Variants that were built and measured slower - two 4-wave workgroups per CU on 256 x 128 tiles,
-//  32-deep slabs in three or four stages - are described in the design notes, not kept as parameters.)
+// (Built and measured slower, and not kept as parameters: two 4-wave workgroups per CU on 256 x 128
+//  tiles, which move 1.5x the bytes into LDS, -20 %; 32-deep slabs in four stages, -6 %.)
 constexpr int FWD_NWN = 4;               // wave columns
 template <bool ARG, bool DMA>
 __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdParams p) {
