@@ -14,18 +14,30 @@
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller, contiguous row-major,
- *     16-byte aligned.  The library never allocates, frees or keeps device memory.  Its only
- *     state is, per device, one auxiliary stream and two events created by the first backward
- *     call that uses them (small problems run the dW gather beside the dH chain; the work is
- *     forked from and joined back into `stream`, so the caller sees ordinary stream order).
- *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream)
- *     and the call returns without synchronising, except the *_profiled variants.
- *     Both calls can be recorded into a HIP graph on a capturing stream; make one backward call
+ *     16-byte aligned.  The library never allocates, frees or keeps device memory; scratch comes in
+ *     as a caller-owned workspace (lsr_head_workspace_bytes states its size).
+ *   - Work is enqueued on `stream` (lsr_stream_t is HIP's hipStream_t; NULL = the null stream)
+ *     and the call returns without synchronising.
+ *   - State.  The library keeps no per-problem state.  Per device it keeps one auxiliary stream and
+ *     two events, created by the first backward call that uses them and kept until the process ends:
+ *     small problems run the dW/db gather on that stream beside the dH chain, forked from and
+ *     joined back into `stream`, so the caller sees ordinary stream order.  The fork..join enqueue is
+ *     serialised per device by a mutex inside the library, so any number of host threads may call
+ *     into the library concurrently, each on its own stream and buffers (their dW gathers then
+ *     queue up on the one auxiliary stream).  Two calls that share a workspace or an output buffer
+ *     must be ordered by the caller, as for any other stream work.
+ *   - Both calls can be recorded into a HIP graph on a capturing stream; make one backward call
  *     on the device before capturing, so that the auxiliary stream and events already exist.
  *   - Outputs are overwritten; nothing has to be zeroed by the caller.
- *   - All argument checks run on the host before anything is enqueued; on error nothing has
- *     been launched.  The return value is an lsr_status; no exceptions, no abort().
+ *   - All argument checks run on the host before anything is enqueued; an error from a check
+ *     (every status except LSR_ERR_LAUNCH) means nothing has been launched.  LSR_ERR_LAUNCH reports
+ *     a failure of the HIP runtime in the middle of the sequence: earlier kernels of the call may
+ *     have been enqueued, the auxiliary stream has been joined back, outputs are undefined.
+ *     The return value is an lsr_status; no exceptions, no abort().
  *   - Inputs must be finite.  The mask may be arbitrary (not only padding at the end).
+ *
+ * Measurement aids (per-kernel timing, the launch plan, a matrix-core probe) are declared in
+ * lsr_head_measure.h; they are not part of the product boundary.
  */
 #ifndef LSR_HEAD_H
 #define LSR_HEAD_H
@@ -36,6 +48,11 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* HIP's stream handle (hipStream_t is a pointer to this same opaque struct), declared here so that
+ * the header needs no HIP include and stays plain C. */
+struct ihipStream_t;
+typedef struct ihipStream_t* lsr_stream_t;
 
 typedef enum {
     LSR_OK = 0,
@@ -80,7 +97,7 @@ size_t lsr_head_workspace_bytes(const lsr_head_desc* desc, int for_backward);
 int lsr_head_forward(const lsr_head_desc* desc,
                      const void* H, const void* W, const float* bias, const uint8_t* mask,
                      float* Y, int32_t* I,
-                     void* workspace, size_t workspace_bytes, void* stream);
+                     void* workspace, size_t workspace_bytes, lsr_stream_t stream);
 
 /*
  * Backward (Sec. 3 "Backward Pass", Alg. 3), from the saved (Y, I) of the forward:
@@ -96,52 +113,7 @@ int lsr_head_backward(const lsr_head_desc* desc,
                       const void* H, const void* W,
                       const float* dY, const float* Y, const int32_t* I,
                       float* dH, float* dW, float* db,
-                      void* workspace, size_t workspace_bytes, void* stream);
-
-/*
- * Same work as the calls above, with each kernel bracketed by HIP events on `stream`.  The call
- * synchronises the stream and writes the per-kernel times in milliseconds to the HOST array
- * kernel_ms (LSR_PROFILE_SLOTS floats; unused slots are set to 0).  For measurement only.
- *   forward : [0] mask compaction  [1] fused GEMM + max/argmax + activation
- *   backward: [0] bucket count     [1] bucket scan   [2] bucket placement
- *             [3] dH gather        [4] dW/db gather
- */
-#define LSR_PROFILE_SLOTS 8
-int lsr_head_forward_profiled(const lsr_head_desc* desc,
-                              const void* H, const void* W, const float* bias, const uint8_t* mask,
-                              float* Y, int32_t* I,
-                              void* workspace, size_t workspace_bytes, void* stream,
-                              float* kernel_ms);
-int lsr_head_backward_profiled(const lsr_head_desc* desc,
-                               const void* H, const void* W,
-                               const float* dY, const float* Y, const int32_t* I,
-                               float* dH, float* dW, float* db,
-                               void* workspace, size_t workspace_bytes, void* stream,
-                               float* kernel_ms);
-
-/*
- * Measurement aid, not part of the head: what the matrix cores of the current device deliver on
- * bf16 32x32x16 MFMAs issued from registers alone (no memory traffic), at the clock the part
- * sustains under that load.  Runs `launches` back-to-back launches of `iters` rounds per wave on
- * `stream` (two waves per SIMD, four independent accumulator chains each), times the last one with
- * events, synchronises, and writes dense TFLOP/s to the HOST double *tflops.  `sink` is a DEVICE
- * pointer to 4 writable bytes (never written in practice; it keeps the arithmetic alive).
- * iters in [1, 2^24], launches in [1, 64].
- */
-int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, void* stream);
-
-/*
- * The launch plan the host derives from a shape alone, for inspection and tests (no device needed,
- * nothing is launched).  Writes LSR_PLAN_SLOTS int32 values to the HOST array `plan`:
- *   [0] row groups of the packed forward          [1] segments of the bucket sort per sequence
- *   [2] vocabulary entries per sort segment       [3] 1 if the sort places through LDS, else 0
- *   [4] vocabulary chunks of the dH gather        [5] vocabulary entries per chunk
- *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
- *   [7] rows of the sliced dW gather's staging tile (0: whole-row dW kernel)
- *   [8] sequences per launch of the sliced dW gather (B: one launch)
- */
-#define LSR_PLAN_SLOTS 9
-int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
+                      void* workspace, size_t workspace_bytes, lsr_stream_t stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* lsr_status_string(int status);

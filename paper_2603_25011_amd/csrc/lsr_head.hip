@@ -1,6 +1,7 @@
 // C ABI of the MI355X sparse-lexical LM head: host-side validation, workspace layout and kernel
 // launches.  See include/lsr_head.h for the contract of every entry point.
 #include "lsr_head.h"
+#include "lsr_head_measure.h"
 
 #include <hip/hip_runtime.h>
 #include <string.h>
@@ -28,8 +29,8 @@ int check_desc(const lsr_head_desc* d, Shape* out) {
     if (d->hw_dtype != LSR_F32 && d->hw_dtype != LSR_BF16) return LSR_ERR_DTYPE;
     if (d->B < 1 || d->S < 1 || d->D < 1 || d->V < 1) return LSR_ERR_SHAPE;
     if (d->D % 8 != 0 || d->D > 8192 || d->S > 32768 || d->B > 65535) return LSR_ERR_SHAPE;
+    if (d->V >= (int64_t(1) << 31) - 4096) return LSR_ERR_SHAPE;      // every factor is bounded before a product is formed
     if (d->B * d->S >= (int64_t(1) << 31) || d->B * d->V >= (int64_t(1) << 31)) return LSR_ERR_SHAPE;
-    if (d->V >= (int64_t(1) << 31) - 4096) return LSR_ERR_SHAPE;
     out->B = (int)d->B; out->S = (int)d->S; out->D = (int)d->D; out->V = (int)d->V;
     out->dtype = d->hw_dtype;
     return LSR_OK;
@@ -208,8 +209,6 @@ struct Prof {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : LSR_ERR_LAUNCH; }
 
-// Loader choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab, else the
-// register-staged loader that can zero-fill the last slab.
 // Kernel choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab and H and W are
 // each below 4 GiB (32-bit byte offsets per lane), else the register-staged loader (64-bit addresses,
 // zero-fills the last slab).
@@ -231,7 +230,7 @@ void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
 }
 
 int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
-                 const uint8_t* mask, float* Y, int32_t* I, void* ws, size_t ws_bytes, void* stream,
+                 const uint8_t* mask, float* Y, int32_t* I, void* ws, size_t ws_bytes, hipStream_t st,
                  Prof& prof) {
     Shape s;
     int rc = check_desc(desc, &s);
@@ -245,7 +244,6 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
     rc = check_device(&n_cus);
     if (rc != LSR_OK) return rc;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     prof.stream = st;
     int* len = reinterpret_cast<int*>(static_cast<char*>(ws) + w.len_off);
     int* pos = reinterpret_cast<int*>(static_cast<char*>(ws) + w.pos_off);
@@ -319,36 +317,125 @@ void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const
 // backward while the gathers are small (B=256 S=32 |V|=30522: 0.42 -> 0.30 ms; B=16 S=256
 // |V|=250002: 1.56 -> 1.47 ms) and lengthens it once they stream tens of GB (B=64 S=512
 // |V|=250002: 7.2 -> 7.7 ms, the two kernels evict each other's L2-resident slices), so it is used
-// up to AUX_MAX_GATHER_BYTES of worst-case gather traffic (2 * B * |V| rows of D elements).  One auxiliary stream and two events per
-// device, created at the first backward on that device and kept until the process ends (default
-// priority, non-blocking with respect to the null stream).
+// up to AUX_MAX_GATHER_BYTES of worst-case gather traffic (2 * B * |V| rows of D elements).
+//
+// The lane (one stream, one fork and one join event per device, default priority, non-blocking with
+// respect to the null stream) is created by the first backward on that device and kept until the
+// process ends.  It is shared by every caller on the device, so a call holds the lane's mutex from the
+// record of the fork event to the wait on the join event: the three enqueue steps that name the
+// shared events (record fork on the caller's stream, wait for it on the lane, ... record join on the
+// lane, wait for it on the caller's stream) can then not interleave with another host thread's, and
+// a wait always refers to the record made by the same call (a stream wait binds to the event's most
+// recent record at the time of the wait call).  Only enqueueing is serialised; the device work of
+// two callers still overlaps as their streams allow, except that their dW gathers share one lane.
 constexpr double AUX_MAX_GATHER_BYTES = 16e9;
 struct AuxLane {
+    std::mutex mu;
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
     bool ready = false;
 };
-AuxLane* aux_lane() {
+AuxLane* aux_lane_of_current_device() {
     static AuxLane lanes[64];
-    static std::mutex mu;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return nullptr; }
-    std::lock_guard<std::mutex> lock(mu);
-    AuxLane& a = lanes[dev];
-    if (!a.ready) {
-        if (hipStreamCreateWithFlags(&a.stream, hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) {
-            (void)hipGetLastError();
-            return nullptr;
+    return &lanes[dev];
+}
+// Holds the lane from fork to join.  forked() is false when the lane could not be used; the caller
+// then runs everything on its own stream.
+class AuxFork {
+public:
+    AuxFork(AuxLane* lane, hipStream_t main) : main_(main) {
+        if (!lane) return;
+        lock_ = std::unique_lock<std::mutex>(lane->mu);
+        if (!lane->ready) {
+            if (hipStreamCreateWithFlags(&lane->stream, hipStreamNonBlocking) != hipSuccess ||
+                hipEventCreateWithFlags(&lane->fork, hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&lane->join, hipEventDisableTiming) != hipSuccess) {
+                (void)hipGetLastError();
+                lock_.unlock();
+                return;
+            }
+            lane->ready = true;
         }
-        a.ready = true;
+        if (hipEventRecord(lane->fork, main) != hipSuccess || hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            lock_.unlock();
+            return;
+        }
+        lane_ = lane;
     }
-    return &a;
+    bool forked() const { return lane_ != nullptr; }
+    hipStream_t side() const { return lane_ ? lane_->stream : main_; }
+    // Joins the lane back into the caller's stream; called on every path once forked, errors included,
+    // so that the caller's stream (possibly one that is being captured) is never left with an open fork.
+    int join() {
+        if (!lane_) return LSR_OK;
+        const bool ok = hipEventRecord(lane_->join, lane_->stream) == hipSuccess &&
+                        hipStreamWaitEvent(main_, lane_->join, 0) == hipSuccess;
+        if (!ok) (void)hipGetLastError();
+        lane_ = nullptr;
+        lock_.unlock();
+        return ok ? LSR_OK : LSR_ERR_LAUNCH;
+    }
+    ~AuxFork() { (void)join(); }
+private:
+    hipStream_t main_;
+    AuxLane* lane_ = nullptr;
+    std::unique_lock<std::mutex> lock_;
+};
+
+// Everything the backward launches is decided here, from the shape alone, before anything is enqueued.
+struct BwdLaunch {
+    int cpt;                 // 16-byte chunks per thread of the whole-row kernels
+    bool staged_place;       // the bucket sort places through LDS
+    bool dh_sliced;          // column-sliced dH gather (D a multiple of 64)
+    int bpw, dh_groups;      // buckets per wave and workgroups per slice of the sliced dH gather
+    int dw_vt;               // rows of the dW staging tile: sliced gather if dw_sliced, else whole-row kernel
+    bool dw_sliced;
+    int dw_bc, dw_ndc, dw_slice_groups, dw_vtiles;
+};
+int plan_backward(const Shape& s, const BwdWs& w, BwdLaunch* L) {
+    const int chunk_elems = s.dtype == LSR_F32 ? 4 : 8;
+    const int n_chunks = s.D / chunk_elems;
+    L->cpt = 1;
+    while (L->cpt * ROW_THREADS < n_chunks) L->cpt *= 2;
+    L->staged_place = s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG;      // plan[3] of lsr_head_plan
+    L->dh_sliced = s.D % DWS_COLS == 0;
+    L->bpw = L->dh_sliced ? dh_buckets_per_wave(s, w.n_vc) : 0;
+    L->dh_groups = L->dh_sliced ? s.B * ((s.S + 4 * L->bpw - 1) / (4 * L->bpw)) : 0;
+    if ((long long)L->dh_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
+    // column-sliced dW gathers (L2-resident slices of H) need D % 64 == 0 and a (g, I) staging tile (at
+    // most 48 KiB) at least 16 vocabulary rows wide, i.e. at most 384 sequences per launch.  Larger
+    // batches keep the whole-row kernel, which also skips zero gradients.
+    L->dw_vt = dw_tile_rows(s);
+    L->dw_sliced = L->dw_vt > 0;
+    L->dw_bc = dw_batch_chunk(s);
+    if (L->dw_sliced) {
+        // slices per group: a workgroup walks the slices of its group with one staging of (g, I), and
+        // the groups run one after the other.  Up to 9 MiB of H rows per group measured best (C5: two
+        // 4 MiB slices, dW 2.21 -> 2.02 ms; C3 0.22 -> 0.175; 3 per group at C5 2.11, all 16: 2.48):
+        // fewer stagings against a wider window of H in flight.
+        const int n_dc = s.D / DWS_COLS;
+        const size_t slice_bytes = (size_t)L->dw_bc * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
+        int ndc = (int)((size_t)(9u << 20) / slice_bytes);
+        L->dw_ndc = ndc < 1 ? 1 : (ndc > n_dc ? n_dc : ndc);
+        L->dw_slice_groups = (n_dc + L->dw_ndc - 1) / L->dw_ndc;
+        L->dw_vtiles = (s.V + L->dw_vt - 1) / L->dw_vt;
+        if ((long long)L->dw_vtiles * L->dw_slice_groups > 0x7fffffffll) return LSR_ERR_SHAPE;
+    } else {
+        // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
+        int VT = 32;
+        while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
+        L->dw_vt = VT;
+        L->dw_ndc = L->dw_slice_groups = 0;
+        L->dw_vtiles = (s.V + VT - 1) / VT;
+    }
+    return LSR_OK;
 }
 
 int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
-                  const int32_t* I, float* dH, float* dW, float* db, void* ws, size_t ws_bytes, void* stream,
+                  const int32_t* I, float* dH, float* dW, float* db, void* ws, size_t ws_bytes, hipStream_t st,
                   Prof& prof) {
     Shape s;
     int rc = check_desc(desc, &s);
@@ -360,140 +447,112 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     if (s.S > 8192 || s.B > 6144) return LSR_ERR_SHAPE;      // LDS tables of the bucket sort / dW staging
     const BwdWs w = bwd_ws(s);
     if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
+    BwdLaunch L;
+    if ((rc = plan_backward(s, w, &L)) != LSR_OK) return rc;
     int n_cus = 0;
     rc = check_device(&n_cus);
     if (rc != LSR_OK) return rc;
+    // ---- nothing has been enqueued up to here; every check is behind us ----
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     prof.stream = st;
     char* base = static_cast<char*>(ws);
     uint2* perm = reinterpret_cast<uint2*>(base + w.perm_off);
     int* cnt = reinterpret_cast<int*>(base + w.cnt_off);
     int* bstart = reinterpret_cast<int*>(base + w.bs_off);
 
-    const int chunk_elems = s.dtype == LSR_F32 ? 4 : 8;
-    const int n_chunks = s.D / chunk_elems;
-    int cpt = 1;
-    while (cpt * ROW_THREADS < n_chunks) cpt *= 2;
-
     // fork: dW/db on the auxiliary stream, the dH chain on the caller's
-    hipStream_t st_main = st;
-    hipStream_t st_dw = st;
     const double gather_bytes = 2.0 * s.B * s.V * s.D * (s.dtype == LSR_F32 ? 4 : 2);
-    AuxLane* lane = (!prof.on && dH && (dW || db) && gather_bytes <= AUX_MAX_GATHER_BYTES) ? aux_lane() : nullptr;
-    if (lane) {
-        if (hipEventRecord(lane->fork, st_main) != hipSuccess || hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess) {
-            (void)hipGetLastError();
-            lane = nullptr;
-        } else {
-            st_dw = lane->stream;
-        }
-    }
+    const bool overlap = !prof.on && dH && (dW || db) && gather_bytes <= AUX_MAX_GATHER_BYTES;
+    AuxFork lane(overlap ? aux_lane_of_current_device() : nullptr, st);
+    const hipStream_t st_dw = lane.side();
 
-    if (dH) {
-        const dim3 seg_grid(w.n_seg, s.B);
-        prof.begin(0);
-        hipLaunchKernelGGL(bwd_count_kernel, seg_grid, dim3(256), sizeof(int) * s.S, st, dY, Y, I, cnt, s.S, s.V, w.n_seg, w.seg_len);
-        prof.end(0);
-        if ((rc = launch_status()) != LSR_OK) return rc;
-        prof.begin(1);
-        hipLaunchKernelGGL(bwd_scan_kernel, dim3(s.B), dim3(256), sizeof(int) * (s.S + 256), st, cnt, bstart, s.S, w.n_seg);
-        prof.end(1);
-        if ((rc = launch_status()) != LSR_OK) return rc;
-        prof.begin(2);
-        if (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG)      // plan[3] of lsr_head_plan
-            hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
-                               dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
-        else
-            hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
-                               s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
-        prof.end(2);
-        if ((rc = launch_status()) != LSR_OK) return rc;
-        prof.begin(3);
-        if (s.D % DWS_COLS == 0) {
-            // column-sliced gathers, one launch per vocabulary chunk: the rows of W in use stay in L2
-            const int* bounds = bstart;
-            if (w.n_vc > 1) {
-                int* cb = reinterpret_cast<int*>(base + w.cb_off);
-                const long long n = (long long)s.B * s.S * (w.n_vc + 1);
-                hipLaunchKernelGGL(bwd_chunk_bounds_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bstart, perm, cb,
-                                   s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
-                bounds = cb;
-            }
-            const int bpw = dh_buckets_per_wave(s, w.n_vc);
-            const int n_groups = s.B * ((s.S + 4 * bpw - 1) / (4 * bpw));
-            if ((long long)n_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
-            const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
-            for (int vc = 0; vc < w.n_vc; ++vc) {
+    // A failed launch ends the sequence; the join below still runs.
+    rc = [&]() -> int {
+        int r;
+        if (dH) {
+            const dim3 seg_grid(w.n_seg, s.B);
+            prof.begin(0);
+            hipLaunchKernelGGL(bwd_count_kernel, seg_grid, dim3(256), sizeof(int) * s.S, st, dY, Y, I, cnt, s.S, s.V, w.n_seg, w.seg_len);
+            prof.end(0);
+            if ((r = launch_status()) != LSR_OK) return r;
+            prof.begin(1);
+            hipLaunchKernelGGL(bwd_scan_kernel, dim3(s.B), dim3(256), sizeof(int) * (s.S + 256), st, cnt, bstart, s.S, w.n_seg);
+            prof.end(1);
+            if ((r = launch_status()) != LSR_OK) return r;
+            prof.begin(2);
+            if (L.staged_place)
+                hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
+                                   dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+            else
+                hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
+                                   s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+            prof.end(2);
+            if ((r = launch_status()) != LSR_OK) return r;
+            prof.begin(3);
+            if (L.dh_sliced) {
+                // column-sliced gathers, one launch per vocabulary chunk: the rows of W in use stay in L2
+                const int* bounds = bstart;
+                if (w.n_vc > 1) {
+                    int* cb = reinterpret_cast<int*>(base + w.cb_off);
+                    const long long n = (long long)s.B * s.S * (w.n_vc + 1);
+                    hipLaunchKernelGGL(bwd_chunk_bounds_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bstart, perm, cb,
+                                       s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
+                    bounds = cb;
+                }
+                const int bpw = L.bpw, n_groups = L.dh_groups;
+                const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
+                for (int vc = 0; vc < w.n_vc; ++vc) {
 #define LSR_DH(T, BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW>), grid, dim3(256), 0, st, static_cast<const T*>(W), bounds, \
                                           perm, dH, s.B, s.S, s.D, s.V, n_groups, w.n_vc, vc)
-                if (s.dtype == LSR_F32) {
-                    if (bpw == 1) LSR_DH(float, 1); else if (bpw == 2) LSR_DH(float, 2); else LSR_DH(float, 4);
-                } else {
-                    if (bpw == 1) LSR_DH(uint16_t, 1); else if (bpw == 2) LSR_DH(uint16_t, 2);
-                    else if (bpw == 4) LSR_DH(uint16_t, 4); else LSR_DH(uint16_t, 8);
-                }
+                    if (s.dtype == LSR_F32) {
+                        if (bpw == 1) LSR_DH(float, 1); else if (bpw == 2) LSR_DH(float, 2); else LSR_DH(float, 4);
+                    } else {
+                        if (bpw == 1) LSR_DH(uint16_t, 1); else if (bpw == 2) LSR_DH(uint16_t, 2);
+                        else if (bpw == 4) LSR_DH(uint16_t, 4); else LSR_DH(uint16_t, 8);
+                    }
 #undef LSR_DH
+                }
+            } else {
+                const dim3 grid(s.B, s.S);
+                if (s.dtype == LSR_F32) launch_dh<float>(L.cpt, grid, st, static_cast<const float*>(W), bstart, perm, dH, s.S, s.D, s.V);
+                else launch_dh<uint16_t>(L.cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm, dH, s.S, s.D, s.V);
             }
-        } else {
-            const dim3 grid(s.B, s.S);
-            if (s.dtype == LSR_F32) launch_dh<float>(cpt, grid, st, static_cast<const float*>(W), bstart, perm, dH, s.S, s.D, s.V);
-            else launch_dh<uint16_t>(cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm, dH, s.S, s.D, s.V);
+            prof.end(3);
+            if ((r = launch_status()) != LSR_OK) return r;
         }
-        prof.end(3);
-        if ((rc = launch_status()) != LSR_OK) return rc;
-    }
-    if (dW || db) {
-        prof.begin(4);
-        // column-sliced gathers (L2-resident slices of H) need D % 64 == 0 and a (g, I) staging tile (at
-        // most 48 KiB) at least 16 vocabulary rows wide, i.e. B <= 384.  Larger batches keep the
-        // whole-row kernel, which also skips zero gradients.
-        int VT = dw_tile_rows(s);
-        if (VT > 0) {
-            // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
-            // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
-            const int waves = 4;
-            const int bc = dw_batch_chunk(s);                  // sequences per launch
-            const size_t lds = (size_t)bc * VT * 8;
-            const int n_vtiles = (s.V + VT - 1) / VT;
-            // slices per group: a workgroup walks the slices of its group with one staging of (g, I), and
-            // the groups run one after the other.  Up to 9 MiB of H rows per group measured best (C5: two
-            // 4 MiB slices, dW 2.21 -> 2.02 ms; C3 0.22 -> 0.175; 3 per group at C5 2.11, all 16: 2.48):
-            // fewer stagings against a wider window of H in flight.
-            const int n_dc = s.D / DWS_COLS;
-            const size_t slice_bytes = (size_t)bc * s.S * DWS_COLS * (s.dtype == LSR_F32 ? 4 : 2);
-            int NDC = (int)((size_t)(9u << 20) / slice_bytes);
-            NDC = NDC < 1 ? 1 : (NDC > n_dc ? n_dc : NDC);
-            const int n_groups = (n_dc + NDC - 1) / NDC;
-            const dim3 grid((unsigned)n_vtiles * (unsigned)n_groups), block(64 * waves);
+        if (dW || db) {
+            prof.begin(4);
+            const int VT = L.dw_vt;
+            if (L.dw_sliced) {
+                // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
+                // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
+                const int waves = 4;
+                const int bc = L.dw_bc;                            // sequences per launch
+                const size_t lds = (size_t)bc * VT * 8;
+                const int n_vtiles = L.dw_vtiles, NDC = L.dw_ndc;
+                const dim3 grid((unsigned)n_vtiles * (unsigned)L.dw_slice_groups), block(64 * waves);
 #define LSR_DW(T, C) hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, C>), grid, block, lds, st_dw, static_cast<const T*>(H), dY, Y, I, \
                                        dW, db, b0, nb, b0 > 0 ? 1 : 0, s.S, s.D, s.V, VT, n_vtiles, NDC)
-            for (int b0 = 0; b0 < s.B; b0 += bc) {
-                const int nb = s.B - b0 < bc ? s.B - b0 : bc;
-                // tiles of 16 rows (more than 192 sequences per launch) compact their columns to the non-zero gradients first
-                if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
-                else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
-            }
+                for (int b0 = 0; b0 < s.B; b0 += bc) {
+                    const int nb = s.B - b0 < bc ? s.B - b0 : bc;
+                    // tiles of 16 rows (more than 192 sequences per launch) compact their columns to the non-zero gradients first
+                    if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
+                    else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
+                }
 #undef LSR_DW
-        } else {
-            // whole-row gathers; rows of the (g, I) staging tile: as wide as 48 KiB of LDS allows, at most 32
-            VT = 32;
-            while (VT > 1 && (size_t)s.B * VT * 8 > 48 * 1024) VT /= 2;
-            const size_t lds = (size_t)s.B * VT * 8;
-            const dim3 grid((s.V + VT - 1) / VT);
-            if (s.dtype == LSR_F32) launch_dw<float>(cpt, grid, lds, st_dw, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
-            else launch_dw<uint16_t>(cpt, grid, lds, st_dw, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+            } else {
+                const size_t lds = (size_t)s.B * VT * 8;
+                const dim3 grid(L.dw_vtiles);
+                if (s.dtype == LSR_F32) launch_dw<float>(L.cpt, grid, lds, st_dw, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+                else launch_dw<uint16_t>(L.cpt, grid, lds, st_dw, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
+            }
+            prof.end(4);
+            if ((r = launch_status()) != LSR_OK) return r;
         }
-        prof.end(4);
-        if ((rc = launch_status()) != LSR_OK) return rc;
-    }
-    if (lane) {      // join
-        if (hipEventRecord(lane->join, st_dw) != hipSuccess || hipStreamWaitEvent(st_main, lane->join, 0) != hipSuccess) {
-            (void)hipGetLastError();
-            return LSR_ERR_LAUNCH;
-        }
-    }
-    return LSR_OK;
+        return LSR_OK;
+    }();
+    const int rj = lane.join();
+    return rc != LSR_OK ? rc : rj;
 }
 
 }  // namespace
@@ -507,21 +566,21 @@ size_t lsr_head_workspace_bytes(const lsr_head_desc* desc, int for_backward) {
 }
 
 int lsr_head_forward(const lsr_head_desc* desc, const void* H, const void* W, const float* bias, const uint8_t* mask,
-                     float* Y, int32_t* I, void* workspace, size_t workspace_bytes, void* stream) {
+                     float* Y, int32_t* I, void* workspace, size_t workspace_bytes, lsr_stream_t stream) {
     Prof prof;
     return forward_impl(desc, H, W, bias, mask, Y, I, workspace, workspace_bytes, stream, prof);
 }
 
 int lsr_head_backward(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
                       const int32_t* I, float* dH, float* dW, float* db, void* workspace, size_t workspace_bytes,
-                      void* stream) {
+                      lsr_stream_t stream) {
     Prof prof;
     return backward_impl(desc, H, W, dY, Y, I, dH, dW, db, workspace, workspace_bytes, stream, prof);
 }
 
 int lsr_head_forward_profiled(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
                               const uint8_t* mask, float* Y, int32_t* I, void* workspace, size_t workspace_bytes,
-                              void* stream, float* kernel_ms) {
+                              lsr_stream_t stream, float* kernel_ms) {
     if (!kernel_ms) return LSR_ERR_NULL;
     Prof prof;
     prof.on = true;
@@ -532,7 +591,7 @@ int lsr_head_forward_profiled(const lsr_head_desc* desc, const void* H, const vo
 
 int lsr_head_backward_profiled(const lsr_head_desc* desc, const void* H, const void* W, const float* dY,
                                const float* Y, const int32_t* I, float* dH, float* dW, float* db, void* workspace,
-                               size_t workspace_bytes, void* stream, float* kernel_ms) {
+                               size_t workspace_bytes, lsr_stream_t stream, float* kernel_ms) {
     if (!kernel_ms) return LSR_ERR_NULL;
     Prof prof;
     prof.on = true;
@@ -541,13 +600,13 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc, const void* H, const v
     return rc != LSR_OK ? rc : rc2;
 }
 
-int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, void* stream) {
+int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, lsr_stream_t stream) {
     if (!sink || !tflops) return LSR_ERR_NULL;
     if (iters < 1 || iters > (1 << 24) || launches < 1 || launches > 64) return LSR_ERR_SHAPE;
     int n_cus = 0;
     int rc = check_device(&n_cus);
     if (rc != LSR_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = stream;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return LSR_ERR_LAUNCH; }
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return LSR_ERR_LAUNCH; }

@@ -10,7 +10,7 @@ import paper_2603_25011_amd as lsr
 from paper_2603_25011_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "lsr_head.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include"))) if n.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -22,9 +22,11 @@ def lib():
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lsr_[a-z_]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(lsr_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -32,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"lsr_head_forward", "lsr_head_backward", "lsr_head_workspace_bytes", "lsr_status_string",
             "lsr_head_forward_profiled", "lsr_head_backward_profiled", "lsr_mfma_peak_probe"} <= set(names)
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in lsr_head.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
 def test_status_strings(lib):

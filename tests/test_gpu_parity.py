@@ -67,6 +67,20 @@ def test_small_bf16_shapes(B, S, D, V, len_lo):
     print(run_case(inp))
 
 
+@pytest.mark.parametrize("B,S,D,V", [
+    (450, 12, 64, 700),       # more than 384 sequences, D a multiple of 64: whole-row dW kernel beside the sliced dH gather
+    (500, 9, 128, 333),
+    (3000, 4, 64, 130),       # batches in the thousands (the 48 KiB staging tile of dW is two rows wide)
+    (6144, 2, 64, 40),        # the largest batch the backward takes
+])
+def test_large_batches_whole_row_dw_beside_sliced_dh(B, S, D, V):
+    from paper_2603_25011_amd import binding as b
+    plan = b.lsr_head_plan(B, S, D, V, b.LSR_BF16)
+    assert plan["dw_tile_rows"] == 0 and plan["dh_buckets_per_wave"] > 0
+    inp = wl.make_custom(B, S, D, V, seed=B + S, len_lo=1)
+    print(run_case(inp))
+
+
 def test_forward_beyond_the_backward_length_limit():
     # S above 8192 is forward-only
     inp = wl.make_custom(2, 9000, 64, 40, seed=31, len_lo=8000, backward=False)
@@ -179,6 +193,12 @@ def test_autograd_wrapper_matches_direct_calls():
     assert torch.equal(Y, head.Y) and torch.equal(I, head.I)
     Y.backward(head.dY)
     torch.cuda.synchronize()
+    # the wrapper's own outputs against the oracle; dH and dW arrive in the parameters' dtype (bf16), so
+    # they are held to the oracle within one bf16 rounding step instead of the fp32 bound
+    I_np = I.cpu().numpy()
+    print(parity.compare_forward(inp, Y.detach().cpu().numpy(), I_np)[3])
+    print(parity.compare_backward(inp, I_np, H.grad.float().cpu().numpy(), W.grad.float().cpu().numpy(),
+                                  bias.grad.cpu().numpy(), bf16_grads=True))
     # same kernels, same order: float32 results are identical before the cast to the parameter dtype
     assert torch.equal(H.grad, head.dH.to(torch.bfloat16))
     assert torch.equal(W.grad, head.dW.to(torch.bfloat16))
@@ -227,6 +247,45 @@ def test_random_shapes_batched_long_and_wide():
         mask = wl.scattered_mask(rng, B, S, keep=keep)
         print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep}", flush=True)
         run_case(inp, mask=mask)
+
+
+def test_two_host_threads_on_two_streams():
+    """Two host threads call forward + backward concurrently, each on its own stream, buffers and small
+    problem (small problems fork the dW gather onto the library's shared auxiliary stream).  Every call
+    of both threads must match the oracle."""
+    import threading
+    inps = [wl.make_custom(6, 70, 128, 900, seed=101, len_lo=3), wl.make_custom(9, 33, 64, 1500, seed=102, len_lo=1)]
+    errors = []
+    results = [[], []]
+
+    def worker(k):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                head = DeviceHead(inps[k])
+                for it in range(20):
+                    head.poison_outputs()
+                    head.forward()
+                    head.backward()
+                    stream.synchronize()
+                    results[k].append(tuple(t.cpu().numpy().copy() for t in (head.Y, head.I, head.dH, head.dW, head.db)))
+        except Exception as exc:          # surfaced in the main thread
+            errors.append((k, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k, inp in enumerate(inps):
+        assert len(results[k]) == 20
+        Y, I, dH, dW, db = results[k][0]
+        parity.compare_forward(inp, Y, I)
+        parity.compare_backward(inp, I, dH, dW, db)
+        for other in results[k][1:]:      # deterministic kernels: every later call is bit-identical to the checked one
+            for a, b_ in zip(results[k][0], other):
+                assert np.array_equal(a, b_)
 
 
 def test_mfma_probe_reports_a_plausible_rate():
