@@ -62,7 +62,9 @@ typedef enum {
     LSR_ERR_ALIGN = 4,      /* a pointer is not 16-byte aligned                         */
     LSR_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than lsr_head_workspace_bytes  */
     LSR_ERR_ARCH = 6,       /* no usable device, or the current device is not gfx950    */
-    LSR_ERR_LAUNCH = 7      /* the HIP runtime reported a launch/event error            */
+    LSR_ERR_LAUNCH = 7,     /* the HIP runtime reported a launch/event error            */
+    LSR_ERR_STATIC_SCRATCH = 8  /* lsr_head_forward_static: the shape needs more scratch than
+                                   LSR_STATIC_SCRATCH_BYTES                              */
 } lsr_status;
 
 typedef enum { LSR_F32 = 0, LSR_BF16 = 1 } lsr_dtype;
@@ -98,6 +100,22 @@ int lsr_head_forward(const lsr_head_desc* desc,
                      const void* H, const void* W, const float* bias, const uint8_t* mask,
                      float* Y, int32_t* I,
                      void* workspace, size_t workspace_bytes, lsr_stream_t stream);
+
+/*
+ * The forward for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same
+ * kernels, same results as lsr_head_forward; the scratch that call takes as `workspace` lives here in
+ * a static device array of LSR_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until
+ * the process ends).  The call allocates and frees nothing.  A shape whose forward scratch
+ * (lsr_head_workspace_bytes(desc, 0)) exceeds the array is rejected with LSR_ERR_STATIC_SCRATCH before
+ * anything is enqueued.  All calls on one GPU share the one array: calls that may overlap on the
+ * device (different streams, or different host threads) race on it and must be ordered by the caller;
+ * calls on one stream are ordered by the stream.  Nothing in the array has to survive between calls.
+ */
+#define LSR_STATIC_SCRATCH_BYTES (16u << 20)
+int lsr_head_forward_static(const lsr_head_desc* desc,
+                            const void* H, const void* W, const float* bias, const uint8_t* mask,
+                            float* Y, int32_t* I, lsr_stream_t stream);
 
 /*
  * Backward (Sec. 3 "Backward Pass", Alg. 3), from the saved (Y, I) of the forward:

@@ -14,6 +14,7 @@ from typing import Optional
 LSR_F32 = 0
 LSR_BF16 = 1
 LSR_PROFILE_SLOTS = 8
+LSR_STATIC_SCRATCH_BYTES = 16 << 20
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "liblsr_head.so")
@@ -49,6 +50,8 @@ def load_library():
     lib.lsr_head_workspace_bytes.argtypes = [dp, ctypes.c_int]
     lib.lsr_head_forward.restype = ctypes.c_int
     lib.lsr_head_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lsr_head_forward_static.restype = ctypes.c_int
+    lib.lsr_head_forward_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
     lib.lsr_head_backward.restype = ctypes.c_int
     lib.lsr_head_backward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lsr_head_forward_profiled.restype = ctypes.c_int
@@ -114,6 +117,12 @@ def lsr_head_forward(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, workspace, st
     wp, wb = _ws(workspace)
     _check(load_library().lsr_head_forward(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(bias), _ptr(mask), _ptr(Y),
                                            _ptr(I), wp, wb, _stream(stream)))
+
+
+def lsr_head_forward_static(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, stream=None) -> None:
+    d = _desc(B, S, D, V, hw_dtype)
+    _check(load_library().lsr_head_forward_static(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(bias), _ptr(mask), _ptr(Y),
+                                                  _ptr(I), _stream(stream)))
 
 
 def lsr_head_backward(B, S, D, V, hw_dtype, H, W, dY, Y, I, dH, dW, db, workspace, stream=None) -> None:

@@ -12,6 +12,11 @@
 #include "fwd_bf16.hpp"
 #include "fwd_misc.hpp"
 
+// Scratch of lsr_head_forward_static: device memory that lives in the library's code object, one copy
+// per GPU, held until the process ends.  In host code this name is only a stand-in for the symbol; the
+// device address comes from hipGetSymbolAddress (static_scratch below) and is what every launch uses.
+static __device__ __align__(256) unsigned char scratch[LSR_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace lsr;
@@ -172,6 +177,23 @@ int check_device(int* n_cus) {
     if (prop.multiProcessorCount < 1) return LSR_ERR_ARCH;
     *n_cus = prop.multiProcessorCount;
     if (dev >= 0 && dev < 64) ok_dev[dev] = prop.multiProcessorCount;
+    return LSR_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device with that device
+// current (every GPU holds its own copy at its own address).
+int static_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr_of[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return LSR_ERR_ARCH; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return LSR_ERR_LAUNCH; }
+        ptr_of[dev] = p;
+    }
+    *out = ptr_of[dev];
     return LSR_OK;
 }
 
@@ -571,6 +593,24 @@ int lsr_head_forward(const lsr_head_desc* desc, const void* H, const void* W, co
     return forward_impl(desc, H, W, bias, mask, Y, I, workspace, workspace_bytes, stream, prof);
 }
 
+int lsr_head_forward_static(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
+                            const uint8_t* mask, float* Y, int32_t* I, lsr_stream_t stream) {
+    Shape s;
+    const int rc = check_desc(desc, &s);
+    if (rc != LSR_OK) return rc;
+    if (fwd_ws(s).total > (size_t)LSR_STATIC_SCRATCH_BYTES) return LSR_ERR_STATIC_SCRATCH;
+    int n_cus = 0;
+    const int rd = check_device(&n_cus);      // a usable gfx950 device is current before its symbol is looked up
+    if (rd != LSR_OK) return rd;
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != LSR_OK) return rs;
+    // Every word of the scratch that a kernel reads has been written earlier in the same call (lengths,
+    // position lists, block tables), so nothing has to be cleared between calls.
+    Prof prof;
+    return forward_impl(desc, H, W, bias, mask, Y, I, ws, (size_t)LSR_STATIC_SCRATCH_BYTES, stream, prof);
+}
+
 int lsr_head_backward(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
                       const int32_t* I, float* dH, float* dW, float* db, void* workspace, size_t workspace_bytes,
                       lsr_stream_t stream) {
@@ -658,6 +698,7 @@ const char* lsr_status_string(int status) {
         case LSR_ERR_WORKSPACE: return "workspace missing or too small";
         case LSR_ERR_ARCH: return "no gfx950 device";
         case LSR_ERR_LAUNCH: return "HIP launch or event error";
+        case LSR_ERR_STATIC_SCRATCH: return "shape needs more scratch than the static array of lsr_head_forward_static holds";
         default: return "unknown status";
     }
 }
