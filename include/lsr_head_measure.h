@@ -18,7 +18,8 @@ extern "C" {
  * Same work as the calls above, with each kernel bracketed by HIP events on `stream`.  The call
  * synchronises the stream and writes the per-kernel times in milliseconds to the HOST array
  * kernel_ms (LSR_PROFILE_SLOTS floats; unused slots are set to 0).  For measurement only.
- *   forward : [0] mask compaction  [1] fused GEMM + max/argmax + activation
+ *   forward : [0] mask compaction and packing  [1] fused GEMM + max/argmax + activation
+ *             [2] join of the sequences cut by a chunk boundary
  *   backward: [0] bucket count     [1] bucket scan   [2] bucket placement
  *             [3] dH gather        [4] dW/db gather
  */
@@ -47,16 +48,36 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc,
 int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops, lsr_stream_t stream);
 
 /*
+ * Measurement aids, not part of the head: reference rates the benchmark quotes beside the backward's
+ * gathers.  Both run `launches` back-to-back launches on `stream` (1..64), time the last one with events,
+ * synchronise, and write a rate in GB/s (1e9 bytes per second) to the HOST double *gbytes_per_s.
+ *
+ * lsr_copy_probe: a plain copy of `bytes` (a multiple of 16) from the DEVICE buffer src to the DEVICE
+ *   buffer dst; the rate counts bytes read plus bytes written.  Also the known-size reference for the
+ *   profiler's FETCH_SIZE / WRITE_SIZE counters.
+ * lsr_gather_probe: 128-byte row pieces gathered at pseudo-random rows of the first window_bytes (a
+ *   multiple of 128) of the DEVICE buffer `table`, eight lanes per piece, four pieces in flight per
+ *   lane, `steps` rounds per lane, fp32 FMAs on the bf16 payload - the access pattern of the backward's
+ *   sliced gathers without their index lists.  The rate counts gathered bytes.  `out` is a DEVICE buffer
+ *   of at least CUs * 16 * 256 * 32 bytes (32 MiB on 256 compute units; LSR_ERR_WORKSPACE if out_bytes
+ *   is smaller); it receives the partial sums.
+ */
+int lsr_copy_probe(void* dst, const void* src, size_t bytes, int launches, double* gbytes_per_s, lsr_stream_t stream);
+int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int launches, void* out, size_t out_bytes,
+                     double* gbytes_per_s, lsr_stream_t stream);
+
+/*
  * The launch plan the host derives from a shape alone, for inspection and tests (no device needed,
  * nothing is launched).  Writes LSR_PLAN_SLOTS int32 values to the HOST array `plan`:
- *   [0] row groups of the packed forward          [1] segments of the bucket sort per sequence
+ *   [0] tiles per chunk of the packed forward     [1] segments of the bucket sort per sequence
  *   [2] vocabulary entries per sort segment       [3] 1 if the sort places through LDS, else 0
  *   [4] vocabulary chunks of the dH gather        [5] vocabulary entries per chunk
  *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
  *   [7] rows of the sliced dW gather's staging tile (0: whole-row dW kernel)
  *   [8] sequences per launch of the sliced dW gather (B: one launch)
+ *   [9] chunks the forward grid provides for (the longest block list the shape allows)
  */
-#define LSR_PLAN_SLOTS 9
+#define LSR_PLAN_SLOTS 10
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
 
 #ifdef __cplusplus

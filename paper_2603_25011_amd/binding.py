@@ -60,6 +60,10 @@ def load_library():
     lib.lsr_head_plan.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)]
     lib.lsr_mfma_peak_probe.restype = ctypes.c_int
     lib.lsr_mfma_peak_probe.argtypes = [ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.lsr_copy_probe.restype = ctypes.c_int
+    lib.lsr_copy_probe.argtypes = [vp, vp, sz, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
+    lib.lsr_gather_probe.restype = ctypes.c_int
+    lib.lsr_gather_probe.argtypes = [vp, sz, ctypes.c_int, ctypes.c_int, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
     lib.lsr_head_backward_profiled.restype = ctypes.c_int
     lib.lsr_head_backward_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, fp]
     lib.lsr_status_string.restype = ctypes.c_char_p
@@ -141,8 +145,9 @@ def lsr_head_forward_profiled(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, work
     return list(ms)
 
 
-LSR_PLAN_FIELDS = ("fwd_row_groups", "sort_segments", "sort_segment_len", "sort_places_through_lds",
-                   "dh_chunks", "dh_chunk_len", "dh_buckets_per_wave", "dw_tile_rows", "dw_sequences_per_launch")
+LSR_PLAN_FIELDS = ("fwd_tiles_per_chunk", "sort_segments", "sort_segment_len", "sort_places_through_lds",
+                   "dh_chunks", "dh_chunk_len", "dh_buckets_per_wave", "dw_tile_rows", "dw_sequences_per_launch",
+                   "fwd_chunks")
 
 
 def lsr_head_plan(B, S, D, V, hw_dtype):
@@ -158,6 +163,21 @@ def lsr_mfma_peak_probe(iters, launches, sink, stream=None):
     out = ctypes.c_double(0.0)
     _check(load_library().lsr_mfma_peak_probe(int(iters), int(launches), _ptr(sink), ctypes.byref(out), _stream(stream)))
     return out.value
+
+
+def lsr_copy_probe(dst, src, nbytes, launches=3, stream=None):
+    """GB/s (read + written) of a plain device copy of nbytes (measurement aid)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().lsr_copy_probe(_ptr(dst), _ptr(src), int(nbytes), int(launches), ctypes.byref(out), _stream(stream)))
+    return out.value
+
+
+def lsr_gather_probe(table, window_bytes, steps, out, launches=3, stream=None):
+    """GB/s of 128-byte row pieces gathered at random rows of a window of the table (measurement aid)."""
+    rate = ctypes.c_double(0.0)
+    _check(load_library().lsr_gather_probe(_ptr(table), int(window_bytes), int(steps), int(launches), _ptr(out),
+                                           out.numel() * out.element_size(), ctypes.byref(rate), _stream(stream)))
+    return rate.value
 
 
 def lsr_head_backward_profiled(B, S, D, V, hw_dtype, H, W, dY, Y, I, dH, dW, db, workspace, stream=None):

@@ -46,20 +46,13 @@ __global__ __launch_bounds__(PREP_THREADS) void fwd_prep_kernel(const uint8_t* _
 
 // Packing plan for the MFMA forward.  Every sequence takes ceil(len / 32) blocks of 32 rows (one
 // block if it has no valid token, so that its zero output is still written); blk0 is the exclusive
-// prefix sum of the block counts, and the block list is cut into n_groups contiguous ranges of whole
-// sequences with about equal block counts, the cuts nudged so that groups hold whole 8-block tiles
-// where a sequence start allows it.  One workgroup; B and n_groups (at most PLAN_MAX_GROUPS) are small
+// prefix sum of the block counts and blk0[B] the length of the block list.  One workgroup; B is small
 // next to the GEMM.
 constexpr int PLAN_THREADS = 256;
-constexpr int PLAN_CAND = 5;            // sequence starts proposed per boundary: the even cut and two either side
-constexpr int PLAN_MAX_GROUPS = 1024;
 
-__global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __restrict__ len, int* blk0,
-                                                                 int* __restrict__ grp_blk0, int B,
-                                                                 int n_groups, int nudge) {
+__global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __restrict__ len, int* __restrict__ blk0,
+                                                                 int B) {
     __shared__ int s_scan[PLAN_THREADS];
-    __shared__ __attribute__((aligned(16))) int s_cand[(PLAN_MAX_GROUPS + 1) * 8];    // PLAN_CAND used of 8 per boundary
-    __shared__ int s_cut[PLAN_MAX_GROUPS + 1];          // even cuts, then the chosen boundaries
     const int tid = threadIdx.x;
     int base = 0;
     for (int b0 = 0; b0 < B; b0 += PLAN_THREADS) {
@@ -82,74 +75,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
         __syncthreads();
     }
     if (tid == 0) blk0[B] = base;
-    // the prefix sums are read back below by other threads of this workgroup: make them visible at
-    // device scope and read them with device-scope loads (no stale line of the vector L1)
-    __threadfence();
-    __syncthreads();
-    const int total = base;
-    auto blk0_at = [&](int b) { return __hip_atomic_load(&blk0[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    // Every thread proposes, for its boundaries, the sequence starts around the even cut
-    // g * total / n_groups; one thread then walks the boundaries in order and takes, among the
-    // proposals within half a group of the even cut, the one that leaves the fewest empty block slots
-    // in the last 8-block tile of the group it closes (ties: nearest to the even cut).  A group whose
-    // block count is a multiple of 8 has no ragged tile; a ragged tile pays the whole vocabulary-tile
-    // side of a tile (loads of W, its fragments, barriers, epilogue) for a fraction of the rows.
-    // The nudged groups are less even in size, so the host asks for them (`nudge`) only when the grid
-    // is many workgroups per CU deep.
-    for (int g = tid; g <= n_groups; g += PLAN_THREADS) {
-        const int target = (int)(((long long)g * total) / n_groups);
-        int lo = 0, hi = B;                       // smallest b in [0, B] with blk0[b] >= target
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (blk0_at(mid) >= target) hi = mid; else lo = mid + 1;
-        }
-        if (!nudge) {                             // even cuts: no boundary depends on another
-            grp_blk0[g] = g == n_groups ? total : blk0_at(lo);
-            continue;
-        }
-        s_cut[g] = target;
-#pragma unroll
-        for (int k = 0; k < PLAN_CAND; ++k) {
-            const int c = lo + k - PLAN_CAND / 2;
-            s_cand[g * 8 + k] = (c >= 0 && c <= B) ? blk0_at(c) : -1;
-        }
-    }
-    __syncthreads();
-    if (nudge && tid == 0) {
-        const int half = total / (2 * n_groups);
-        int prev = 0;
-        for (int g = 1; g < n_groups; ++g) {
-            const int target = s_cut[g];
-            // the proposals of this boundary in two 16-byte reads, then branch-free selection
-            const int4 c03 = *reinterpret_cast<const int4*>(&s_cand[g * 8]);
-            const int c4 = s_cand[g * 8 + 4];
-            const int cand[PLAN_CAND] = {c03.x, c03.y, c03.z, c03.w, c4};
-            int best = -1, best_key = 0x7fffffff;
-#pragma unroll
-            for (int k = 0; k < PLAN_CAND; ++k) {
-                const int x = cand[k];
-                const int dist = x > target ? x - target : target - x;
-                const bool ok = x > prev && (dist <= half || k == PLAN_CAND / 2);
-                const int waste = (8 - ((x - prev) & 7)) & 7;
-                const int key = ok ? (waste << 27) | (dist < (1 << 27) ? dist : (1 << 27) - 1) : 0x7fffffff;
-                const bool take = key < best_key;
-                best_key = take ? key : best_key;
-                best = take ? x : best;
-            }
-            prev = best < 0 ? prev : best;        // nothing beyond the last boundary: an empty group
-            s_cut[g] = prev;
-        }
-        s_cut[0] = 0;
-        s_cut[n_groups] = total;
-    }
-    __syncthreads();
-    if (nudge)
-        for (int g = tid; g <= n_groups; g += PLAN_THREADS) grp_blk0[g] = s_cut[g];
 }
 
 // Row table of the packed layout, one workgroup per sequence: packed row k of the sequence reads
 // token pos[min(k, len-1)] (the tail of the last block repeats the last valid token), and every
-// block records its sequence, whether it ends it, and whether the sequence is empty.
+// block records its sequence and whether it begins it, ends it, and whether the sequence is empty.
 constexpr int FWD_ROWS_THREADS = 256;
 
 __global__ __launch_bounds__(FWD_ROWS_THREADS) void fwd_rows_kernel(const int* __restrict__ len,
@@ -167,7 +97,122 @@ __global__ __launch_bounds__(FWD_ROWS_THREADS) void fwd_rows_kernel(const int* _
         rows[(size_t)g0 * 32 + k] = make_int2(b * S + s, s);
     }
     for (int k = threadIdx.x; k < nblk; k += FWD_ROWS_THREADS)
-        blk_meta[g0 + k] = b | (k == nblk - 1 ? (1 << 31) : 0) | (n == 0 ? (1 << 30) : 0);
+        blk_meta[g0 + k] = b | (k == nblk - 1 ? FWD_META_LAST : 0) | (n == 0 ? FWD_META_EMPTY : 0) |
+                           (k == 0 ? FWD_META_FIRST : 0);
+}
+
+// The three passes above in one launch of one workgroup, for batches of few tokens (the host takes
+// this path up to PACK_MAX_TOKENS mask entries and PACK_MAX_B sequences), where three dependent
+// launches cost more than the work in them.  Wave w serves sequences w, w + 16, ...: it compacts the
+// mask row (ballot + popcount), and after the workgroup-wide prefix sum of the block counts writes the
+// row table and block records of the same sequences (its own earlier stores, program order).
+constexpr int PACK_THREADS = 1024;
+constexpr int PACK_MAX_B = 4096;
+constexpr int PACK_MAX_TOKENS = 32768;
+
+__global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* __restrict__ mask, int* __restrict__ len,
+                                                                 int* __restrict__ pos, int* __restrict__ blk0,
+                                                                 int2* __restrict__ rows, int* __restrict__ blk_meta,
+                                                                 int B, int S) {
+    __shared__ int s_len[PACK_MAX_B];
+    __shared__ int s_blk0[PACK_MAX_B + 1];
+    __shared__ int s_part[PACK_THREADS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = PACK_THREADS / 64;
+    // 1. compaction
+    for (int b = wave; b < B; b += NW) {
+        const uint8_t* mrow = mask + (size_t)b * S;
+        int* prow = pos + (size_t)b * S;
+        int base = 0;
+        for (int s0 = 0; s0 < S; s0 += 64) {
+            const int s = s0 + lane;
+            const bool flag = s < S && mrow[s] != 0;
+            const unsigned long long bal = __ballot(flag);
+            if (flag) prow[base + __popcll(bal & ((1ull << lane) - 1ull))] = s;
+            base += __popcll(bal);
+        }
+        if (lane == 0) { s_len[b] = base; len[b] = base; }
+    }
+    __syncthreads();
+    // 2. exclusive prefix sum of the block counts: consecutive sequences per thread, then the partials
+    const int per = (B + PACK_THREADS - 1) / PACK_THREADS;
+    const int lo = min(B, tid * per), hi = min(B, lo + per);
+    int sum = 0;
+    for (int b = lo; b < hi; ++b) sum += max(1, (s_len[b] + 31) >> 5);
+    s_part[tid] = sum;
+    __syncthreads();
+    for (int off = 1; off < PACK_THREADS; off <<= 1) {
+        const int add = tid >= off ? s_part[tid - off] : 0;
+        __syncthreads();
+        s_part[tid] += add;
+        __syncthreads();
+    }
+    int run = s_part[tid] - sum;
+    for (int b = lo; b < hi; ++b) {
+        s_blk0[b] = run;
+        blk0[b] = run;
+        run += max(1, (s_len[b] + 31) >> 5);
+    }
+    if (tid == PACK_THREADS - 1) { s_blk0[B] = s_part[tid]; blk0[B] = s_part[tid]; }
+    __syncthreads();
+    // 3. row table and block records
+    for (int b = wave; b < B; b += NW) {
+        const int n = s_len[b];
+        const int g0 = s_blk0[b];
+        const int nblk = s_blk0[b + 1] - g0;
+        const int* prow = pos + (size_t)b * S;
+        for (int k = lane; k < nblk * 32; k += 64) {
+            const int s = n > 0 ? prow[k < n ? k : n - 1] : 0;
+            rows[(size_t)g0 * 32 + k] = make_int2(b * S + s, s);
+        }
+        for (int k = lane; k < nblk; k += 64)
+            blk_meta[g0 + k] = b | (k == nblk - 1 ? FWD_META_LAST : 0) | (n == 0 ? FWD_META_EMPTY : 0) |
+                               (k == 0 ? FWD_META_FIRST : 0);
+    }
+}
+
+// Joins the pieces of the sequences that a chunk boundary of the fused kernel cuts (see fwd_bf16.hpp).
+// The workgroups of chunk c leave, for a sequence that runs on into chunk c+1, the raw (max, position)
+// of its blocks inside chunk c in Y and I; the workgroups of every later chunk k the sequence reaches
+// leave theirs in slot k of part_m / part_s.  One thread per (chunk, vocabulary entry) takes the
+// pieces in order (later pieces hold higher positions, so an equal maximum keeps the earlier
+// position), applies bias, ReLU and log1p (F4) and overwrites Y and I with the final values.
+// grid (ceil(V/256), chunks the host provides for).  tpc = most tiles per chunk (ChunkSplit).
+constexpr int FWD_MERGE_THREADS = 256;
+
+template <bool ARG>
+__global__ __launch_bounds__(FWD_MERGE_THREADS) void fwd_merge_kernel(const int* __restrict__ blk0,
+                                                                       const int* __restrict__ blk_meta,
+                                                                       const float* __restrict__ part_m,
+                                                                       const int* __restrict__ part_s,
+                                                                       const float* __restrict__ bias,
+                                                                       float* __restrict__ Y, int* __restrict__ I,
+                                                                       int B, int V, int tpc) {
+    const int c = blockIdx.y;
+    const int n_blocks = blk0[B];
+    const ChunkSplit cs = chunk_split(n_blocks, tpc);
+    if (c >= cs.nc) return;
+    const int c_lo = cs.first_tile(c) * FWD_TB;
+    const int c_hi = min(n_blocks, cs.first_tile(c + 1) * FWD_TB);     // first block behind the chunk
+    const int meta = blk_meta[c_hi - 1];
+    if (meta & FWD_META_LAST) return;                                  // the chunk ends with a sequence
+    const int b = meta & FWD_META_SEQ;
+    if (blk0[b] < c_lo) return;                                        // began in an earlier chunk: joined from there
+    const int k_end = cs.chunk_of_tile((blk0[b + 1] - 1) / FWD_TB);    // chunk that holds the sequence's last block
+    const int v = blockIdx.x * FWD_MERGE_THREADS + threadIdx.x;
+    if (v >= V) return;
+    const size_t o = (size_t)b * V + v;
+    float m = Y[o];
+    int s = ARG ? I[o] : 0;
+    for (int k = c + 1; k <= k_end; ++k) {
+        const float pm = part_m[(size_t)k * V + v];
+        if (pm > m) {
+            m = pm;
+            if (ARG) s = part_s[(size_t)k * V + v];
+        }
+    }
+    Y[o] = log1pf(fmaxf(m + bias[v], 0.f));
+    if (ARG) I[o] = s;
 }
 
 // Plain fp32 head: one thread per (b, v), looping over valid positions and the hidden size with

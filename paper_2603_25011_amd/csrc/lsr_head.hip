@@ -11,6 +11,7 @@
 #include "bwd.hpp"
 #include "fwd_bf16.hpp"
 #include "fwd_misc.hpp"
+#include "probes.hpp"
 
 // Scratch of lsr_head_forward_static: device memory that lives in the library's code object, one copy
 // per GPU, held until the process ends.  In host code this name is only a stand-in for the symbol; the
@@ -43,37 +44,49 @@ int check_desc(const lsr_head_desc* d, Shape* out) {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// ---- forward workspace: len[B] | pos[B*S] | blk0[B+1] | grp_blk0[groups+1] | blk_meta[blocks] |
-//      rows[blocks*32], blocks = B * ceil(S/32) being the most the packed layout can need ----
-constexpr int FWD_MAX_GROUPS = PLAN_MAX_GROUPS;
-struct FwdWs { size_t len_off, pos_off, blk0_off, grp_off, meta_off, rows_off, total; };
+// Chunks of the packed forward (see fwd_bf16.hpp).  The host does not know the lengths, so it sizes the
+// grid and the workspace for the longest block list the shape allows (every sequence full:
+// B * ceil(S/32) blocks, 8 per tile); chunks beyond the real list return at once.
+// Tiles per chunk: a workgroup that walks several tiles hides the start of each behind the one before
+// (row tables and the first slab are prefetched), but leaves fewer, longer workgroups to balance over
+// the chip.  At most four per chunk measured best or within 1.5 % of best on every benchmark shape
+// (forward ms with 1 / 2 / 4 / 8: B=32 S=256 |V|=30522 0.289 / 0.281 / 0.280 / 0.312; B=256 S=32 0.364 /
+// 0.361 / 0.345 / 0.341; B=16 S=256 |V|=250002 0.966 / 0.944 / 0.958 / 1.007; B=64 S=512 D=1024 8.91 / 8.92 /
+// 8.78 / 8.95), the kernel then splitting the real tiles evenly over the chunks.  Never more chunks than
+// sequences: the per-chunk slots for cut sequences (8 bytes per vocabulary entry) then stay below the
+// size of the outputs Y and I, whatever the sequence length.
+struct FwdChunks { int tpc, n_chunks; bool cut_possible; };
+FwdChunks fwd_chunks(const Shape& s) {
+    const long blocks_max = (long)s.B * ((s.S + 31) / 32);
+    const long tiles_max = (blocks_max + FWD_TB - 1) / FWD_TB;
+    FwdChunks c;
+    c.tpc = 4;
+    const long per_seq = (tiles_max + s.B - 1) / s.B;
+    if (c.tpc < per_seq) c.tpc = (int)per_seq;
+    c.n_chunks = (int)((tiles_max + c.tpc - 1) / c.tpc);
+    // a sequence of one block can never lie across a chunk boundary: no pieces, no merge pass
+    c.cut_possible = s.S > FWD_BLK && c.n_chunks > 1;
+    return c;
+}
+
+// ---- forward workspace: len[B] | pos[B*S] | blk0[B+1] | blk_meta[blocks] | rows[blocks*32] |
+//      part_m[chunks*V] | part_s[chunks*V]; blocks = B * ceil(S/32) being the most the packed layout can
+//      need, the two part arrays only where a chunk boundary can fall inside a sequence ----
+struct FwdWs { size_t len_off, pos_off, blk0_off, meta_off, rows_off, pm_off, ps_off, total; };
 FwdWs fwd_ws(const Shape& s) {
     FwdWs w;
     const size_t blocks = (size_t)s.B * ((s.S + 31) / 32);
+    const FwdChunks c = fwd_chunks(s);
+    const size_t part = (s.dtype == LSR_BF16 && c.cut_possible) ? align_up(sizeof(float) * (size_t)c.n_chunks * s.V) : 0;
     w.len_off = 0;
     w.pos_off = w.len_off + align_up(sizeof(int) * (size_t)s.B);
     w.blk0_off = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
-    w.grp_off = w.blk0_off + align_up(sizeof(int) * ((size_t)s.B + 1));
-    w.meta_off = w.grp_off + align_up(sizeof(int) * (FWD_MAX_GROUPS + 1));
+    w.meta_off = w.blk0_off + align_up(sizeof(int) * ((size_t)s.B + 1));
     w.rows_off = w.meta_off + align_up(sizeof(int) * blocks);
-    w.total = w.rows_off + align_up(sizeof(int2) * blocks * 32);
+    w.pm_off = w.rows_off + align_up(sizeof(int2) * blocks * 32);
+    w.ps_off = w.pm_off + part;
+    w.total = w.ps_off + part;
     return w;
-}
-
-// Row groups of the packed forward: about four tiles (32 blocks) per group, which measured best
-// over the shipped workloads (many groups: more workgroups to balance; few groups: fewer short last
-// tiles and more reuse of a vocabulary tile).  Lengths are not known on the host, so the block count
-// is an estimate: sequences are taken to fill 70 % of S, and every sequence has at least one block.
-int fwd_row_groups(const Shape& s) {
-    const long per_seq_max = (s.S + 31) / 32;
-    long per_seq10 = per_seq_max * 7;                    // tenths of a block
-    if (per_seq10 < 10) per_seq10 = 10;
-    const long blocks = (long)s.B * per_seq10 / 10;
-    long ng = (blocks + 16) / 32;
-    if (ng > s.B) ng = s.B;
-    if (ng > FWD_MAX_GROUPS) ng = FWD_MAX_GROUPS;
-    if (ng < 1) ng = 1;
-    return (int)ng;
 }
 
 // ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] |
@@ -239,7 +252,7 @@ void launch_fwd_cfg(FwdParams p, int V, bool arg, hipStream_t st) {
     constexpr int TN = fwd_tn(FWD_NWN);
     p.n_vtiles = (V + TN - 1) / TN;
     p.gv = FWD_GV_COLS / TN;
-    p.n_logical = (p.n_vtiles + p.gv - 1) / p.gv * p.gv * p.n_rowgroups;
+    p.n_logical = (p.n_vtiles + p.gv - 1) / p.gv * p.gv * p.n_chunks;
     const dim3 grid((p.n_logical + 7) / 8 * 8), block(fwd_threads(FWD_NWN));
     if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA>), grid, block, 0, st, p);
     else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA>), grid, block, 0, st, p);
@@ -271,19 +284,20 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
     int* pos = reinterpret_cast<int*>(static_cast<char*>(ws) + w.pos_off);
 
     prof.begin(0);
-    hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
+    // batches of few tokens are packed by one workgroup in one launch (bf16 path)
+    const bool one_launch = s.dtype == LSR_BF16 && s.B <= PACK_MAX_B && (long)s.B * s.S <= PACK_MAX_TOKENS;
+    if (!one_launch) hipLaunchKernelGGL(fwd_prep_kernel, dim3(s.B), dim3(PREP_THREADS), 0, st, mask, len, pos, s.S);
     char* base = static_cast<char*>(ws);
     int* blk0 = reinterpret_cast<int*>(base + w.blk0_off);
-    int* grp_blk0 = reinterpret_cast<int*>(base + w.grp_off);
     int* blk_meta = reinterpret_cast<int*>(base + w.meta_off);
     int2* rows = reinterpret_cast<int2*>(base + w.rows_off);
-    const int n_rowgroups = fwd_row_groups(s);
-    if (s.dtype == LSR_BF16) {
-        // cuts nudged to whole tiles: C5 (84 workgroups per CU) 9.16 -> 9.04 ms, C4 (11) 0.926 -> 0.898;
-        // C2 (2.8 per CU) loses 7 % to the less even groups
-        const long n_wg = (long)n_rowgroups * ((s.V + 255) / 256);
-        const int nudge = n_wg >= 8l * n_cus ? 1 : 0;
-        hipLaunchKernelGGL(fwd_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, len, blk0, grp_blk0, s.B, n_rowgroups, nudge);
+    float* part_m = reinterpret_cast<float*>(base + w.pm_off);
+    int* part_s = reinterpret_cast<int*>(base + w.ps_off);
+    const FwdChunks ck = fwd_chunks(s);
+    if (one_launch) {
+        hipLaunchKernelGGL(fwd_pack_kernel, dim3(1), dim3(PACK_THREADS), 0, st, mask, len, pos, blk0, rows, blk_meta, s.B, s.S);
+    } else if (s.dtype == LSR_BF16) {
+        hipLaunchKernelGGL(fwd_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, len, blk0, s.B);
         hipLaunchKernelGGL(fwd_rows_kernel, dim3(s.B), dim3(FWD_ROWS_THREADS), 0, st, len, pos, blk0, rows, blk_meta, s.S);
     }
     prof.end(0);
@@ -300,12 +314,23 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         FwdParams p;
         p.H = static_cast<const uint16_t*>(H);
         p.W = static_cast<const uint16_t*>(W);
-        p.bias = bias; p.rows = rows; p.blk_meta = blk_meta; p.grp_blk0 = grp_blk0; p.Y = Y; p.I = I;
+        p.bias = bias; p.rows = rows; p.blk_meta = blk_meta; p.n_blocks = blk0 + s.B; p.Y = Y; p.I = I;
+        p.part_m = part_m; p.part_s = part_s;
         p.B = s.B; p.S = s.S; p.D = s.D; p.V = s.V;
-        p.n_rowgroups = n_rowgroups;
+        p.n_chunks = ck.n_chunks; p.tpc = ck.tpc;
         launch_fwd_bf16(p, I != nullptr, st);
     }
     prof.end(1);
+    if (s.dtype == LSR_BF16 && ck.cut_possible) {
+        if ((rc = launch_status()) != LSR_OK) return rc;
+        prof.begin(2);
+        const dim3 grid((s.V + FWD_MERGE_THREADS - 1) / FWD_MERGE_THREADS, ck.n_chunks);
+        if (I) hipLaunchKernelGGL((fwd_merge_kernel<true>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
+                                  bias, Y, I, s.B, s.V, ck.tpc);
+        else   hipLaunchKernelGGL((fwd_merge_kernel<false>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
+                                  bias, Y, I, s.B, s.V, ck.tpc);
+        prof.end(2);
+    }
     return launch_status();
 }
 
@@ -577,6 +602,28 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     return rc != LSR_OK ? rc : rj;
 }
 
+// Runs `launch` `launches` times on st and returns the duration of the last one in ms (< 0 on error).
+template <typename F>
+float time_last_launch(int launches, hipStream_t st, F&& launch) {
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return -1.f; }
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return -1.f; }
+    bool ok = true;
+    for (int l = 0; l < launches && ok; ++l) {
+        const bool timed = l + 1 == launches;
+        if (timed) ok = hipEventRecord(e0, st) == hipSuccess;
+        launch();
+        ok = ok && hipGetLastError() == hipSuccess;
+        if (timed) ok = ok && hipEventRecord(e1, st) == hipSuccess;
+    }
+    float ms = -1.f;
+    ok = ok && hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (!ok) { (void)hipGetLastError(); return -1.f; }
+    return ms;
+}
+
 }  // namespace
 
 extern "C" {
@@ -670,13 +717,56 @@ int lsr_mfma_peak_probe(int64_t iters, int launches, void* sink, double* tflops,
     return LSR_OK;
 }
 
+int lsr_copy_probe(void* dst, const void* src, size_t bytes, int launches, double* gbytes_per_s, lsr_stream_t stream) {
+    if (!dst || !src || !gbytes_per_s) return LSR_ERR_NULL;
+    if (misaligned(dst) || misaligned(src)) return LSR_ERR_ALIGN;
+    if (bytes < 16 || bytes % 16 != 0 || launches < 1 || launches > 64) return LSR_ERR_SHAPE;
+    int n_cus = 0;
+    const int rc = check_device(&n_cus);
+    if (rc != LSR_OK) return rc;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + COPY_THREADS - 1) / COPY_THREADS;
+    const size_t cap = (size_t)n_cus * 32;            // grid-stride loop over a grid that fills the chip a few times
+    if (blocks > cap) blocks = cap;
+    const float ms = time_last_launch(launches, stream, [&] {
+        hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream, static_cast<uint4*>(dst),
+                           static_cast<const uint4*>(src), n16);
+    });
+    if (ms <= 0.f) return LSR_ERR_LAUNCH;
+    *gbytes_per_s = 2.0 * (double)bytes / (ms * 1e-3) / 1e9;      // bytes read + bytes written
+    return LSR_OK;
+}
+
+int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int launches, void* out, size_t out_bytes,
+                     double* gbytes_per_s, lsr_stream_t stream) {
+    if (!table || !out || !gbytes_per_s) return LSR_ERR_NULL;
+    if (misaligned(table) || misaligned(out)) return LSR_ERR_ALIGN;
+    if (window_bytes < 128 || window_bytes % 128 != 0 || window_bytes > ((size_t)1 << 38) || steps < 1 || steps > (1 << 20) ||
+        launches < 1 || launches > 64)
+        return LSR_ERR_SHAPE;
+    int n_cus = 0;
+    const int rc = check_device(&n_cus);
+    if (rc != LSR_OK) return rc;
+    const unsigned blocks = (unsigned)n_cus * 16;                // eight waves resident per SIMD's worth of work in flight
+    const size_t groups = (size_t)blocks * GATHER_THREADS / 8;
+    if (out_bytes < groups * 8 * 8 * sizeof(float)) return LSR_ERR_WORKSPACE;
+    const uint32_t rows = (uint32_t)(window_bytes / 128);
+    const float ms = time_last_launch(launches, stream, [&] {
+        hipLaunchKernelGGL(gather_probe_kernel, dim3(blocks), dim3(GATHER_THREADS), 0, stream, static_cast<const uint16_t*>(table),
+                           rows, steps, static_cast<float*>(out));
+    });
+    if (ms <= 0.f) return LSR_ERR_LAUNCH;
+    *gbytes_per_s = (double)groups * steps * GATHER_NLD * 128.0 / (ms * 1e-3) / 1e9;
+    return LSR_OK;
+}
+
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     Shape s;
     const int rc = check_desc(desc, &s);
     if (rc != LSR_OK) return rc;
     if (!plan) return LSR_ERR_NULL;
     const BwdWs w = bwd_ws(s);
-    plan[0] = fwd_row_groups(s);
+    plan[0] = fwd_chunks(s).tpc;
     plan[1] = w.n_seg;
     plan[2] = w.seg_len;
     plan[3] = (s.S <= PLACE_MAX_S && w.seg_len <= PLACE_MAX_SEG) ? 1 : 0;
@@ -685,6 +775,7 @@ int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     plan[6] = s.D % DWS_COLS == 0 ? dh_buckets_per_wave(s, w.n_vc) : 0;
     plan[7] = dw_tile_rows(s);
     plan[8] = dw_batch_chunk(s);
+    plan[9] = fwd_chunks(s).n_chunks;
     return LSR_OK;
 }
 

@@ -45,10 +45,14 @@ def test_status_strings(lib):
 
 def test_workspace_sizes_scale_as_documented(lib):
     f = lsr.lsr_head_workspace_bytes
-    # forward: O(B*S); backward: O(B*V); nothing proportional to B*S*V
+    # forward: O(B*S) tables + 8 bytes per vocabulary entry and chunk of tiles (never more chunks than
+    # sequences); backward: O(B*V); nothing proportional to B*S*V
     fw = f(64, 512, 1024, 250002, lsr.LSR_BF16, False)
     bw = f(64, 512, 1024, 250002, lsr.LSR_BF16, True)
-    assert 4 * 64 * 512 <= fw <= 16 * 64 * 512 + 16384
+    assert 4 * 64 * 512 <= fw <= 16 * 64 * 512 + 16384 + 8 * 250002 * (64 * 512 // 1024 + 1)
+    assert fw < 8 * 64 * 250002                           # below the size of the outputs Y and I
+    long_s = f(128, 8192, 768, 30522, lsr.LSR_BF16, False)
+    assert long_s <= 16 * 128 * 8192 + 8 * 128 * 30522 + 16384
     assert 8 * 64 * 250002 <= bw <= 16 * 64 * 250002
     assert bw < 64 * 512 * 250002 // 8
     # long sequences do not blow up the backward count table
