@@ -98,7 +98,7 @@ def time_workload(name, steps, warmup, torch, wl, DeviceHead, rotate=False):
         comp = (3 * w.B * w.V * 4 + w.B * w.S * w.D * esz + w.V * w.D * esz + w.V * w.D * 4 + w.B * w.S * w.D * 4 + w.V * 4)
         res["bwd_compulsory_bytes"] = int(comp)
         res["bwd_gbs_compulsory"] = comp / (bwd_ms * 1e-3) / 1e9
-        res["bwd_gather_bytes_cache_level"] = int(2 * 2 * nnz * w.D * esz)      # rows of H for dW + rows of W for dH
+        res["bwd_gather_bytes_cache_level"] = int(2 * nnz * w.D * esz)      # nnz rows of H for dW + nnz rows of W for dH
         res["bwd_cache"] = "warm: the same buffers every step"
     # Per-kernel times from the event-bracketed entry points.  Each profiled call synchronises, and a
     # kernel that starts on an idle device runs at a lower clock for its first part (a profiled forward

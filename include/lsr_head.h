@@ -133,6 +133,35 @@ int lsr_head_backward(const lsr_head_desc* desc,
                       float* dH, float* dW, float* db,
                       void* workspace, size_t workspace_bytes, lsr_stream_t stream);
 
+/*
+ * The backward with options (Sec. 5 trains through the head: gradients usually go straight into
+ * bfloat16 parameter gradients, and are accumulated over micro-batches).
+ *   grad_dtype  LSR_F32: dH and dW are float32 (as lsr_head_backward).  LSR_BF16 (needs hw_dtype =
+ *               LSR_BF16): dH [B,S,D] and dW [V,D] are bfloat16.  Sums are formed in float32 in the same
+ *               order as for float32 outputs and rounded to nearest-even once, when the final value is
+ *               stored; a result that several launches add up keeps its float32 partial sums in the
+ *               workspace meanwhile.  db is float32 in both cases.
+ *   accumulate  0: every requested output is overwritten.  1: the gradients are added to what dH, dW and
+ *               db hold on entry (out = out + gradient, one rounding for bfloat16); positions of dH that
+ *               receive no gradient are left as they are.
+ * opts == NULL means {LSR_F32, 0}.  The workspace size for given options comes from
+ * lsr_head_backward_ex_workspace_bytes (0 for an invalid desc or option); for {LSR_F32, any} it equals
+ * lsr_head_workspace_bytes(desc, 1).  Everything else as lsr_head_backward.
+ */
+typedef struct {
+    int32_t grad_dtype;   /* lsr_dtype of dH and dW */
+    int32_t accumulate;   /* 0 or 1 */
+} lsr_backward_opts;
+
+size_t lsr_head_backward_ex_workspace_bytes(const lsr_head_desc* desc, const lsr_backward_opts* opts);
+
+int lsr_head_backward_ex(const lsr_head_desc* desc,
+                         const void* H, const void* W,
+                         const float* dY, const float* Y, const int32_t* I,
+                         void* dH, void* dW, float* db,
+                         const lsr_backward_opts* opts,
+                         void* workspace, size_t workspace_bytes, lsr_stream_t stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsr_status_string(int status);
 

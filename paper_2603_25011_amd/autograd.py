@@ -37,17 +37,18 @@ class _LsrHead(torch.autograd.Function):
         need_h, need_w, need_b = ctx.needs_input_grad[0], ctx.needs_input_grad[1], ctx.needs_input_grad[2]
         dY = dY.contiguous().float()
         dev = H.device
-        dH = torch.empty((B, S, D), dtype=torch.float32, device=dev) if need_h else None
-        dW = torch.empty((V, D), dtype=torch.float32, device=dev) if need_w else None
+        # the library stores dH and dW in the parameters' own dtype (float32 sums, rounded once)
+        dH = torch.empty((B, S, D), dtype=H.dtype, device=dev) if need_h else None
+        dW = torch.empty((V, D), dtype=W.dtype, device=dev) if need_w else None
         db = torch.empty((V,), dtype=torch.float32, device=dev) if need_b else None
         if need_h or need_w or need_b:
-            ws = torch.empty(lsr.lsr_head_workspace_bytes(B, S, D, V, dt, True), dtype=torch.uint8, device=dev)
-            lsr.lsr_head_backward(B, S, D, V, dt, H, W, dY, Y, I, dH, dW, db, ws)
-        return (dH.to(H.dtype) if need_h else None, dW.to(W.dtype) if need_w else None, db, None)
+            ws = torch.empty(lsr.lsr_head_backward_ex_workspace_bytes(B, S, D, V, dt, dt), dtype=torch.uint8, device=dev)
+            lsr.lsr_head_backward_ex(B, S, D, V, dt, H, W, dY, Y, I, dH, dW, db, dt, False, ws)
+        return dH, dW, db, None
 
 
 def lsr_head(H: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, mask: torch.Tensor):
     """Y[b,v] = max over valid s of log(1 + ReLU(H[b,s,:] . W[v,:] + bias[v]))  (Eq. 1), differentiable
     in H, W and bias.  Returns (Y float32 [B,V], I int32 [B,V]); I is the arg-max position.
-    Gradients are computed in float32 and cast to the dtype of the parameter they belong to."""
+    Gradients are summed in float32 and stored by the library in the dtype of the parameter they belong to."""
     return _LsrHead.apply(H, W, bias, mask)

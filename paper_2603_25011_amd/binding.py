@@ -27,6 +27,10 @@ class LsrError(RuntimeError):
         self.status = status
 
 
+class _BackwardOpts(ctypes.Structure):
+    _fields_ = [("grad_dtype", ctypes.c_int32), ("accumulate", ctypes.c_int32)]
+
+
 class _Desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int64), ("S", ctypes.c_int64), ("D", ctypes.c_int64), ("V", ctypes.c_int64),
                 ("hw_dtype", ctypes.c_int32)]
@@ -54,6 +58,11 @@ def load_library():
     lib.lsr_head_forward_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
     lib.lsr_head_backward.restype = ctypes.c_int
     lib.lsr_head_backward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    op = ctypes.POINTER(_BackwardOpts)
+    lib.lsr_head_backward_ex.restype = ctypes.c_int
+    lib.lsr_head_backward_ex.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, op, vp, sz, vp]
+    lib.lsr_head_backward_ex_workspace_bytes.restype = sz
+    lib.lsr_head_backward_ex_workspace_bytes.argtypes = [dp, op]
     lib.lsr_head_forward_profiled.restype = ctypes.c_int
     lib.lsr_head_forward_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp, fp]
     lib.lsr_head_plan.restype = ctypes.c_int
@@ -134,6 +143,21 @@ def lsr_head_backward(B, S, D, V, hw_dtype, H, W, dY, Y, I, dH, dW, db, workspac
     wp, wb = _ws(workspace)
     _check(load_library().lsr_head_backward(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(dY), _ptr(Y), _ptr(I),
                                             _ptr(dH), _ptr(dW), _ptr(db), wp, wb, _stream(stream)))
+
+
+def lsr_head_backward_ex_workspace_bytes(B, S, D, V, hw_dtype, grad_dtype=LSR_F32, accumulate=False) -> int:
+    d = _desc(B, S, D, V, hw_dtype)
+    o = _BackwardOpts(int(grad_dtype), 1 if accumulate else 0)
+    return int(load_library().lsr_head_backward_ex_workspace_bytes(ctypes.byref(d), ctypes.byref(o)))
+
+
+def lsr_head_backward_ex(B, S, D, V, hw_dtype, H, W, dY, Y, I, dH, dW, db, grad_dtype, accumulate, workspace,
+                         stream=None) -> None:
+    d = _desc(B, S, D, V, hw_dtype)
+    o = _BackwardOpts(int(grad_dtype), 1 if accumulate else 0)
+    wp, wb = _ws(workspace)
+    _check(load_library().lsr_head_backward_ex(ctypes.byref(d), _ptr(H), _ptr(W), _ptr(dY), _ptr(Y), _ptr(I),
+                                               _ptr(dH), _ptr(dW), _ptr(db), ctypes.byref(o), wp, wb, _stream(stream)))
 
 
 def lsr_head_forward_profiled(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, workspace, stream=None):

@@ -47,6 +47,31 @@ template <> struct RowChunk<uint16_t> {       // bfloat16 storage
     }
 };
 
+// Gradient outputs are float32 or bfloat16 (OT = float or uint16_t): sums are always formed in float32
+// and rounded once, to nearest even, when the final value is stored.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;        // finite inputs
+}
+template <typename OT> struct OutVec;
+template <> struct OutVec<float> {
+    // four consecutive elements
+    static __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ __forceinline__ void store4(float* p, float4 x) { *reinterpret_cast<float4*>(p) = x; }
+};
+template <> struct OutVec<uint16_t> {
+    static __device__ __forceinline__ float4 load4(const uint16_t* p) {
+        const uint2 u = *reinterpret_cast<const uint2*>(p);
+        return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                           __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+    }
+    static __device__ __forceinline__ void store4(uint16_t* p, float4 x) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(f32_to_bf16_bits(x.x) | (f32_to_bf16_bits(x.y) << 16),
+                                                  f32_to_bf16_bits(x.z) | (f32_to_bf16_bits(x.w) << 16));
+    }
+};
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
 // ---------------------------------------------------------------------------------------------
 // Stable bucketing of the non-zero (b,v) pairs by position s.
 // The vocabulary is cut into n_seg segments of seg_len entries; (b, segment) is the unit of work.
@@ -295,12 +320,13 @@ __global__ __launch_bounds__(256) void bwd_place_staged_kernel(const float* __re
 // dH[b,s,:] = sum over the bucket of (b,s), in ascending v, of g * W[v,:].   grid (B, S): b fastest,
 // so that the empty buckets behind the ends of the sequences are spread evenly over the chip
 // ---------------------------------------------------------------------------------------------
-template <typename T, int CPT>
+// accumulate: the sums are added to what dH holds
+template <typename T, int CPT, typename OT>
 __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict__ W,
                                                              const int* __restrict__ bstart,
                                                              const uint2* __restrict__ perm,
-                                                             float* __restrict__ dH,
-                                                             int S, int D, int V) {
+                                                             OT* __restrict__ dH,
+                                                             int S, int D, int V, int accumulate) {
     constexpr int N = RowChunk<T>::N;
     __shared__ int s_v[ROW_THREADS];
     __shared__ float s_g[ROW_THREADS];
@@ -341,15 +367,17 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict
         }
         __syncthreads();
     }
-    float* out = dH + ((size_t)b * S + s) * D;
+    OT* out = dH + ((size_t)b * S + s) * D;
 #pragma unroll
     for (int cp = 0; cp < CPT; ++cp) {
         const int c = tid + cp * ROW_THREADS;
         if (c < n_chunks) {
 #pragma unroll
-            for (int i = 0; i < N; i += 4)
-                *reinterpret_cast<float4*>(out + c * N + i) =
-                    make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+            for (int i = 0; i < N; i += 4) {
+                float4 r = make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+                if (accumulate) r = add4(OutVec<OT>::load4(out + c * N + i), r);
+                OutVec<OT>::store4(out + c * N + i, r);
+            }
         }
     }
 }
@@ -360,13 +388,14 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dh_kernel(const T* __restrict
 // LDS (coalesced along v), then walks the rows one by one, skipping pairs with g = 0.
 // dynamic LDS: B*VT floats + B*VT ints.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int CPT>
+// accumulate: the sums are added to what dW and db hold
+template <typename T, int CPT, typename OT>
 __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict__ H,
                                                              const float* __restrict__ dY,
                                                              const float* __restrict__ Y,
                                                              const int* __restrict__ I,
-                                                             float* __restrict__ dW, float* __restrict__ db,
-                                                             int B, int S, int D, int V, int VT) {
+                                                             OT* __restrict__ dW, float* __restrict__ db,
+                                                             int B, int S, int D, int V, int VT, int accumulate) {
     constexpr int N = RowChunk<T>::N;
     extern __shared__ int s_dyn[];
     float* s_g = reinterpret_cast<float*>(s_dyn);          // [B][VT]
@@ -430,23 +459,25 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
                     for (int cp = 0; cp < CPT; ++cp) RowChunk<T>::fma(x[u][cp], g[u], acc[cp]);
             }
         }
-        float* out = dW + (size_t)v * D;
+        OT* out = dW + (size_t)v * D;
         if (dW) {
 #pragma unroll
             for (int cp = 0; cp < CPT; ++cp) {
                 const int c = tid + cp * ROW_THREADS;
                 if (c < n_chunks) {
 #pragma unroll
-                    for (int i = 0; i < N; i += 4)
-                        *reinterpret_cast<float4*>(out + c * N + i) =
-                            make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+                    for (int i = 0; i < N; i += 4) {
+                        float4 r = make_float4(acc[cp][i], acc[cp][i + 1], acc[cp][i + 2], acc[cp][i + 3]);
+                        if (accumulate) r = add4(OutVec<OT>::load4(out + c * N + i), r);
+                        OutVec<OT>::store4(out + c * N + i, r);
+                    }
                 }
             }
         }
         if (db && tid < 64) {                                    // fixed-order butterfly over b
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o);
-            if (tid == 0) db[v] = gsum;
+            if (tid == 0) db[v] = accumulate ? db[v] + gsum : gsum;
         }
     }
 }
@@ -472,20 +503,26 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // When the H slice of the whole batch (B*S rows x 128 bytes) is larger than L2, the host launches
 // the kernel once per chunk of consecutive sequences (b_first, B = sequences of the chunk); later
 // launches add to dW and db, which keeps the order of the sums fixed.
+// Where the partial sums come from and where the result goes is set per launch: `prev` (float32, may
+// be null) is added to the sums of this launch, `add_dst` adds what dst already holds (accumulation into
+// the caller's gradient), and dst is float32 or bfloat16 (OT).  A float32 result spread over several
+// launches passes prev = dst; a bfloat16 result keeps its partial sums in a float32 staging array (dst of
+// all launches but the last, prev of all but the first), so that it is rounded once.
 // dynamic LDS: B*VT floats + B*VT ints.   grid = ceil(V/VT) * ceil((D/64)/NDC).
 // ---------------------------------------------------------------------------------------------
 constexpr int DWS_COLS = 64;
 
-template <typename T, bool COMPACT>
+template <typename T, bool COMPACT, typename OT>
 __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict__ H,
                                                             const float* __restrict__ dY,
                                                             const float* __restrict__ Y,
                                                             const int* __restrict__ I,
-                                                            float* __restrict__ dW, float* __restrict__ db,
-                                                            int b_first, int B, int add, int S, int D, int V, int VT,
+                                                            const float* prev, OT* dW, int add_dst,
+                                                            float* __restrict__ db, int add_db,
+                                                            int b_first, int B, int S, int D, int V, int VT,
                                                             int n_vtiles, int NDC) {
-    // b_first, B: the sequences of this launch (see below); add: dW and db already hold the sums over
-    // the sequences before b_first and are added to
+    // b_first, B: the sequences of this launch; prev / add_dst: see above; add_db: db already holds the
+    // sums over the sequences before b_first (or the caller's accumulated gradient) and is added to
     constexpr int N = RowChunk<T>::N;          // elements per 16-byte chunk
     constexpr int LPR = DWS_COLS / N;          // lanes per row piece
     constexpr int VPG = 64 / LPR;              // vocabulary rows a wave serves at once
@@ -551,7 +588,7 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
     if (COMPACT) __syncthreads();
 
     if (db && dg == 0 && tid < VT && v0 + tid < V) {           // fixed-order sum over b
-        float sum = add ? db[v0 + tid] : 0.f;
+        float sum = add_db ? db[v0 + tid] : 0.f;
         for (int k = 0; k < B; ++k) {
             const float g = s_g[at(k, tid)];
             if (COMPACT && g == 0.f) break;
@@ -586,15 +623,13 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
                 if (COMPACT && !open) break;
             }
             if (v < V) {
-                float* out = dW + (size_t)v * D + col0;
+                const size_t o = (size_t)v * D + col0;
 #pragma unroll
                 for (int i = 0; i < N; i += 4) {
                     float4 r = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-                    if (add) {
-                        const float4 prev = *reinterpret_cast<const float4*>(out + i);
-                        r = make_float4(prev.x + r.x, prev.y + r.y, prev.z + r.z, prev.w + r.w);
-                    }
-                    *reinterpret_cast<float4*>(out + i) = r;
+                    if (prev) r = add4(*reinterpret_cast<const float4*>(prev + o + i), r);
+                    if (add_dst) r = add4(OutVec<OT>::load4(dW + o + i), r);
+                    OutVec<OT>::store4(dW + o + i, r);
                 }
             }
         }
@@ -616,6 +651,9 @@ __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict_
 // entry list where the chunks begin (bwd_chunk_bounds_kernel); with n_vc = 1 it is the bucket start
 // table itself.  Chunk 0 writes dH (zeros for empty buckets), later chunks add to it: one owner per
 // element and launch, launches in stream order, so the sum keeps a fixed order.
+// As in the dW gather, `prev` (float32, may be null) is added to the sums of this launch, `add_dst` adds
+// what dst already holds, dst is float32 or bfloat16; `write_all` makes every bucket write (the launch
+// that produces the final value of a fresh result), otherwise only buckets with entries in this chunk do.
 // grid = B * ceil(S / (4*BPW)) * (D/64), 256 threads.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void bwd_chunk_bounds_kernel(const int* __restrict__ bstart,
@@ -639,11 +677,11 @@ __global__ __launch_bounds__(256) void bwd_chunk_bounds_kernel(const int* __rest
     bounds[idx] = lo;
 }
 
-template <typename T, int BPW>
+template <typename T, int BPW, typename OT>
 __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict__ W,
                                                             const int* __restrict__ bounds,
                                                             const uint2* __restrict__ perm,
-                                                            float* __restrict__ dH,
+                                                            const float* prev_sum, OT* dH, int add_dst, int write_all,
                                                             int B, int S, int D, int V, int n_groups,
                                                             int n_vc, int vc) {
     constexpr int N = RowChunk<T>::N;
@@ -668,22 +706,27 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
     const size_t bi = n_vc == 1 ? (size_t)b * (S + 1) + s : (size_t)bq * (n_vc + 1) + vc;
     const int beg = live ? bounds[bi] : 0;
     const int end = live ? bounds[bi + 1] : 0;
-    const bool add = vc > 0;
-    if (add && !__any(beg < end)) return;      // nothing of this chunk in any bucket of the wave
+    if (!write_all && !__any(beg < end)) return;      // nothing of this chunk in any bucket of the wave
     const size_t prow = (size_t)b * V;
     const int col0 = dc * DWS_COLS + (lane % LPR) * N;
     const int sub = (lane % G) / LPR;
-    const bool writer = live && sub == 0 && (!add || beg < end);
-    float* out = dH + (size_t)bq * D + col0;
+    const bool writer = live && sub == 0 && (write_all || beg < end);
+    const size_t o = (size_t)bq * D + col0;
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
     float4 prev[N / 4];                        // the sum of the earlier chunks, requested early
 #pragma unroll
     for (int i = 0; i < N / 4; ++i) prev[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (add && writer) {
+    if (writer) {
+        if (prev_sum) {
 #pragma unroll
-        for (int i = 0; i < N / 4; ++i) prev[i] = *reinterpret_cast<const float4*>(out + 4 * i);
+            for (int i = 0; i < N / 4; ++i) prev[i] = *reinterpret_cast<const float4*>(prev_sum + o + 4 * i);
+        }
+        if (add_dst) {
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) prev[i] = add4(prev[i], OutVec<OT>::load4(dH + o + 4 * i));
+        }
     }
     // the (v, g) entries of the next NLD loads are fetched while the current rows are in flight, so
     // the list read and the row gather it feeds never sit in one dependency chain
@@ -720,9 +763,8 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
     if (writer) {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i)
-            *reinterpret_cast<float4*>(out + 4 * i) =
-                make_float4(prev[i].x + acc[4 * i], prev[i].y + acc[4 * i + 1], prev[i].z + acc[4 * i + 2],
-                            prev[i].w + acc[4 * i + 3]);
+            OutVec<OT>::store4(dH + o + 4 * i, make_float4(prev[i].x + acc[4 * i], prev[i].y + acc[4 * i + 1],
+                                                           prev[i].z + acc[4 * i + 2], prev[i].w + acc[4 * i + 3]));
     }
 }
 

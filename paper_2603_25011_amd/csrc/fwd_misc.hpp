@@ -101,14 +101,16 @@ __global__ __launch_bounds__(FWD_ROWS_THREADS) void fwd_rows_kernel(const int* _
                            (k == 0 ? FWD_META_FIRST : 0);
 }
 
-// The three passes above in one launch of one workgroup, for batches of few tokens (the host takes
-// this path up to PACK_MAX_TOKENS mask entries and PACK_MAX_B sequences), where three dependent
-// launches cost more than the work in them.  Wave w serves sequences w, w + 16, ...: it compacts the
+// The three passes above in one launch of one workgroup, for batches of few sequences and tokens (the
+// host takes this path up to PACK_MAX_TOKENS mask entries and PACK_MAX_B sequences), where three
+// dependent launches cost more than the work in them (B=32 S=256: 15.6 -> 11.6 us, B=16 S=256: 13.5 ->
+// 9.8 us; with hundreds of sequences the waves' one-sequence-at-a-time loop loses: B=256 S=32 13.5 ->
+// 21.8 us, B=64 S=512 24 -> 37 us).  Wave w serves sequences w, w + 16, ...: it compacts the
 // mask row (ballot + popcount), and after the workgroup-wide prefix sum of the block counts writes the
 // row table and block records of the same sequences (its own earlier stores, program order).
 constexpr int PACK_THREADS = 1024;
-constexpr int PACK_MAX_B = 4096;
-constexpr int PACK_MAX_TOKENS = 32768;
+constexpr int PACK_MAX_B = 64;
+constexpr int PACK_MAX_TOKENS = 16384;
 
 __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* __restrict__ mask, int* __restrict__ len,
                                                                  int* __restrict__ pos, int* __restrict__ blk0,
@@ -177,8 +179,10 @@ __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* _
 // leave theirs in slot k of part_m / part_s.  One thread per (chunk, vocabulary entry) takes the
 // pieces in order (later pieces hold higher positions, so an equal maximum keeps the earlier
 // position), applies bias, ReLU and log1p (F4) and overwrites Y and I with the final values.
-// grid (ceil(V/256), chunks the host provides for).  tpc = most tiles per chunk (ChunkSplit).
+// grid (ceil(V/256), up to FWD_MERGE_ROWS): a workgroup walks the chunks y, y + gridDim.y, ... (most end
+// with a whole sequence and cost one table read).  tpc = most tiles per chunk (ChunkSplit).
 constexpr int FWD_MERGE_THREADS = 256;
+constexpr int FWD_MERGE_ROWS = 4;
 
 template <bool ARG>
 __global__ __launch_bounds__(FWD_MERGE_THREADS) void fwd_merge_kernel(const int* __restrict__ blk0,
@@ -188,31 +192,31 @@ __global__ __launch_bounds__(FWD_MERGE_THREADS) void fwd_merge_kernel(const int*
                                                                        const float* __restrict__ bias,
                                                                        float* __restrict__ Y, int* __restrict__ I,
                                                                        int B, int V, int tpc) {
-    const int c = blockIdx.y;
     const int n_blocks = blk0[B];
     const ChunkSplit cs = chunk_split(n_blocks, tpc);
-    if (c >= cs.nc) return;
-    const int c_lo = cs.first_tile(c) * FWD_TB;
-    const int c_hi = min(n_blocks, cs.first_tile(c + 1) * FWD_TB);     // first block behind the chunk
-    const int meta = blk_meta[c_hi - 1];
-    if (meta & FWD_META_LAST) return;                                  // the chunk ends with a sequence
-    const int b = meta & FWD_META_SEQ;
-    if (blk0[b] < c_lo) return;                                        // began in an earlier chunk: joined from there
-    const int k_end = cs.chunk_of_tile((blk0[b + 1] - 1) / FWD_TB);    // chunk that holds the sequence's last block
     const int v = blockIdx.x * FWD_MERGE_THREADS + threadIdx.x;
-    if (v >= V) return;
-    const size_t o = (size_t)b * V + v;
-    float m = Y[o];
-    int s = ARG ? I[o] : 0;
-    for (int k = c + 1; k <= k_end; ++k) {
-        const float pm = part_m[(size_t)k * V + v];
-        if (pm > m) {
-            m = pm;
-            if (ARG) s = part_s[(size_t)k * V + v];
+    for (int c = blockIdx.y; c < cs.nc; c += gridDim.y) {
+        const int c_lo = cs.first_tile(c) * FWD_TB;
+        const int c_hi = min(n_blocks, cs.first_tile(c + 1) * FWD_TB);     // first block behind the chunk
+        const int meta = blk_meta[c_hi - 1];
+        if (meta & FWD_META_LAST) continue;                                // the chunk ends with a sequence
+        const int b = meta & FWD_META_SEQ;
+        if (blk0[b] < c_lo) continue;                                      // began in an earlier chunk: joined from there
+        const int k_end = cs.chunk_of_tile((blk0[b + 1] - 1) / FWD_TB);    // chunk that holds the sequence's last block
+        if (v >= V) continue;
+        const size_t o = (size_t)b * V + v;
+        float m = Y[o];
+        int s = ARG ? I[o] : 0;
+        for (int k = c + 1; k <= k_end; ++k) {
+            const float pm = part_m[(size_t)k * V + v];
+            if (pm > m) {
+                m = pm;
+                if (ARG) s = part_s[(size_t)k * V + v];
+            }
         }
+        Y[o] = log1pf(fmaxf(m + bias[v], 0.f));
+        if (ARG) I[o] = s;
     }
-    Y[o] = log1pf(fmaxf(m + bias[v], 0.f));
-    if (ARG) I[o] = s;
 }
 
 // Plain fp32 head: one thread per (b, v), looping over valid positions and the hidden size with

@@ -91,7 +91,7 @@ FwdWs fwd_ws(const Shape& s) {
 
 // ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] |
 //      bounds[B*S*(n_vc+1)] (only when the dH gather is cut into n_vc > 1 vocabulary chunks) ----
-struct BwdWs { int n_seg, seg_len, key_bits, n_vc, vc_len; size_t perm_off, cnt_off, bs_off, cb_off, total; };
+struct BwdWs { int n_seg, seg_len, key_bits, n_vc, vc_len; size_t perm_off, cnt_off, bs_off, cb_off, dh_stage_off, dw_stage_off, total; };
 
 // Vocabulary chunks of the sliced dH gather.  A chunk is sized so that one 64-column slice of its
 // rows of W is about 4 MB (what stays in L2 while every bucket gathers from it).  Each chunk after
@@ -109,7 +109,12 @@ void dh_chunks(const Shape& s, int* n_vc, int* vc_len) {
     *n_vc = (int)c;
     *vc_len = (int)((s.V + c - 1) / c);
 }
-BwdWs bwd_ws(const Shape& s) {
+int dw_batch_chunk(const Shape& s);
+int dw_tile_rows(const Shape& s);
+// bf16_out: dH and dW are stored as bfloat16.  A result that several launches add up (dH over vocabulary
+// chunks, dW over chunks of sequences) then keeps its float32 partial sums in a staging array of the
+// workspace and is rounded once, by the last launch.
+BwdWs bwd_ws(const Shape& s, bool bf16_out = false) {
     BwdWs w;
     // enough (b, segment) waves to fill the chip, segments of at least 512 entries, and a count
     // table no larger than B*V ints
@@ -133,7 +138,10 @@ BwdWs bwd_ws(const Shape& s) {
     w.bs_off = w.cnt_off + align_up(sizeof(int) * (size_t)s.B * w.n_seg * s.S);
     w.cb_off = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
     dh_chunks(s, &w.n_vc, &w.vc_len);
-    w.total = w.cb_off + (w.n_vc > 1 ? align_up(sizeof(int) * (size_t)s.B * s.S * (w.n_vc + 1)) : 0);
+    w.dh_stage_off = w.cb_off + (w.n_vc > 1 ? align_up(sizeof(int) * (size_t)s.B * s.S * (w.n_vc + 1)) : 0);
+    w.dw_stage_off = w.dh_stage_off + ((bf16_out && w.n_vc > 1) ? align_up(sizeof(float) * (size_t)s.B * s.S * s.D) : 0);
+    const bool dw_multi = dw_tile_rows(s) > 0 && dw_batch_chunk(s) < s.B;
+    w.total = w.dw_stage_off + ((bf16_out && dw_multi) ? align_up(sizeof(float) * (size_t)s.V * s.D) : 0);
     return w;
 }
 
@@ -324,7 +332,7 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
     if (s.dtype == LSR_BF16 && ck.cut_possible) {
         if ((rc = launch_status()) != LSR_OK) return rc;
         prof.begin(2);
-        const dim3 grid((s.V + FWD_MERGE_THREADS - 1) / FWD_MERGE_THREADS, ck.n_chunks);
+        const dim3 grid((s.V + FWD_MERGE_THREADS - 1) / FWD_MERGE_THREADS, ck.n_chunks < FWD_MERGE_ROWS ? ck.n_chunks : FWD_MERGE_ROWS);
         if (I) hipLaunchKernelGGL((fwd_merge_kernel<true>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
                                   bias, Y, I, s.B, s.V, ck.tpc);
         else   hipLaunchKernelGGL((fwd_merge_kernel<false>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
@@ -334,28 +342,52 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
     return launch_status();
 }
 
-template <typename T>
+template <typename T, typename OT>
 void launch_dh(int cpt, dim3 grid, hipStream_t st, const T* W, const int* bstart, const uint2* pm,
-               float* dH, int S, int D, int V) {
+               OT* dH, int S, int D, int V, int accumulate) {
     switch (cpt) {
-        case 1: hipLaunchKernelGGL((bwd_dh_kernel<T, 1>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
-        case 2: hipLaunchKernelGGL((bwd_dh_kernel<T, 2>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
-        case 4: hipLaunchKernelGGL((bwd_dh_kernel<T, 4>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
-        case 8: hipLaunchKernelGGL((bwd_dh_kernel<T, 8>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
-        default: hipLaunchKernelGGL((bwd_dh_kernel<T, 16>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V); break;
+        case 1: hipLaunchKernelGGL((bwd_dh_kernel<T, 1, OT>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V, accumulate); break;
+        case 2: hipLaunchKernelGGL((bwd_dh_kernel<T, 2, OT>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V, accumulate); break;
+        case 4: hipLaunchKernelGGL((bwd_dh_kernel<T, 4, OT>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V, accumulate); break;
+        case 8: hipLaunchKernelGGL((bwd_dh_kernel<T, 8, OT>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V, accumulate); break;
+        default: hipLaunchKernelGGL((bwd_dh_kernel<T, 16, OT>), grid, dim3(ROW_THREADS), 0, st, W, bstart, pm, dH, S, D, V, accumulate); break;
     }
 }
 
-template <typename T>
+template <typename T, typename OT>
 void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const float* dY, const float* Y, const int* I,
-               float* dW, float* db, int B, int S, int D, int V, int VT) {
+               OT* dW, float* db, int B, int S, int D, int V, int VT, int accumulate) {
     switch (cpt) {
-        case 1: hipLaunchKernelGGL((bwd_dw_kernel<T, 1>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
-        case 2: hipLaunchKernelGGL((bwd_dw_kernel<T, 2>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
-        case 4: hipLaunchKernelGGL((bwd_dw_kernel<T, 4>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
-        case 8: hipLaunchKernelGGL((bwd_dw_kernel<T, 8>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
-        default: hipLaunchKernelGGL((bwd_dw_kernel<T, 16>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT); break;
+        case 1: hipLaunchKernelGGL((bwd_dw_kernel<T, 1, OT>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT, accumulate); break;
+        case 2: hipLaunchKernelGGL((bwd_dw_kernel<T, 2, OT>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT, accumulate); break;
+        case 4: hipLaunchKernelGGL((bwd_dw_kernel<T, 4, OT>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT, accumulate); break;
+        case 8: hipLaunchKernelGGL((bwd_dw_kernel<T, 8, OT>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT, accumulate); break;
+        default: hipLaunchKernelGGL((bwd_dw_kernel<T, 16, OT>), grid, dim3(ROW_THREADS), lds, st, H, dY, Y, I, dW, db, B, S, D, V, VT, accumulate); break;
     }
+}
+
+// One launch of the sliced dH gather (vocabulary chunk vc) / of the sliced dW gather (sequences b0 .. b0+nb-1).
+template <typename T, typename OT>
+void launch_dh_sliced(int bpw, dim3 grid, hipStream_t st, const T* W, const int* bounds, const uint2* perm, const float* prev,
+                      OT* dst, int add_dst, int write_all, const Shape& s, int n_groups, int n_vc, int vc) {
+#define LSR_DH(BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW, OT>), grid, dim3(256), 0, st, W, bounds, perm, prev, dst, add_dst, \
+                                       write_all, s.B, s.S, s.D, s.V, n_groups, n_vc, vc)
+    if (bpw == 1) LSR_DH(1);
+    else if (bpw == 2) LSR_DH(2);
+    else if (bpw == 4 || sizeof(T) == 4) LSR_DH(4);      // a float row piece takes 16 lanes: at most four buckets per wave
+    else if constexpr (sizeof(T) == 2) LSR_DH(8);
+#undef LSR_DH
+}
+template <typename T, typename OT>
+void launch_dw_sliced(bool compact, dim3 grid, dim3 block, size_t lds, hipStream_t st, const T* H, const float* dY, const float* Y,
+                      const int* I, const float* prev, OT* dst, int add_dst, float* db, int add_db, int b0, int nb, const Shape& s,
+                      int VT, int n_vtiles, int NDC) {
+    if (compact)
+        hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, true, OT>), grid, block, lds, st, H, dY, Y, I, prev, dst, add_dst, db, add_db, b0, nb,
+                           s.S, s.D, s.V, VT, n_vtiles, NDC);
+    else
+        hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, false, OT>), grid, block, lds, st, H, dY, Y, I, prev, dst, add_dst, db, add_db, b0, nb,
+                           s.S, s.D, s.V, VT, n_vtiles, NDC);
 }
 
 // The dW/db gather does not depend on the bucket sort that feeds dH, so the plain (not profiled)
@@ -481,18 +513,29 @@ int plan_backward(const Shape& s, const BwdWs& w, BwdLaunch* L) {
     return LSR_OK;
 }
 
+// The whole backward for element types T (H, W) and OT (dH, dW), after every check.
+template <typename T, typename OT>
+int backward_launches(const Shape& s, const BwdWs& w, const BwdLaunch& L, const T* H, const T* W, const float* dY, const float* Y,
+                      const int32_t* I, OT* dH, OT* dW, float* db, int accumulate, char* base, hipStream_t st, hipStream_t st_dw,
+                      Prof& prof);
+
 int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
-                  const int32_t* I, float* dH, float* dW, float* db, void* ws, size_t ws_bytes, hipStream_t st,
-                  Prof& prof) {
+                  const int32_t* I, void* dH, void* dW, float* db, const lsr_backward_opts* opts, void* ws, size_t ws_bytes,
+                  hipStream_t st, Prof& prof) {
     Shape s;
     int rc = check_desc(desc, &s);
     if (rc != LSR_OK) return rc;
+    const int grad_dtype = opts ? opts->grad_dtype : LSR_F32;
+    const int accumulate = (opts && opts->accumulate) ? 1 : 0;
+    if (grad_dtype != LSR_F32 && grad_dtype != LSR_BF16) return LSR_ERR_DTYPE;
+    if (grad_dtype == LSR_BF16 && s.dtype != LSR_BF16) return LSR_ERR_DTYPE;      // bfloat16 gradients belong to bfloat16 parameters
+    const bool bf16_out = grad_dtype == LSR_BF16;
     if (!H || !W || !dY || !Y || !I) return LSR_ERR_NULL;
     if (misaligned(H) || misaligned(W) || misaligned(dY) || misaligned(Y) || misaligned(I) || misaligned(ws) ||
         (dH && misaligned(dH)) || (dW && misaligned(dW)) || (db && misaligned(db)))
         return LSR_ERR_ALIGN;
     if (s.S > 8192 || s.B > 6144) return LSR_ERR_SHAPE;      // LDS tables of the bucket sort / dW staging
-    const BwdWs w = bwd_ws(s);
+    const BwdWs w = bwd_ws(s, bf16_out);
     if (!ws || ws_bytes < w.total) return LSR_ERR_WORKSPACE;
     BwdLaunch L;
     if ((rc = plan_backward(s, w, &L)) != LSR_OK) return rc;
@@ -503,9 +546,6 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
 
     prof.stream = st;
     char* base = static_cast<char*>(ws);
-    uint2* perm = reinterpret_cast<uint2*>(base + w.perm_off);
-    int* cnt = reinterpret_cast<int*>(base + w.cnt_off);
-    int* bstart = reinterpret_cast<int*>(base + w.bs_off);
 
     // fork: dW/db on the auxiliary stream, the dH chain on the caller's
     const double gather_bytes = 2.0 * s.B * s.V * s.D * (s.dtype == LSR_F32 ? 4 : 2);
@@ -514,92 +554,124 @@ int backward_impl(const lsr_head_desc* desc, const void* H, const void* W, const
     const hipStream_t st_dw = lane.side();
 
     // A failed launch ends the sequence; the join below still runs.
-    rc = [&]() -> int {
-        int r;
-        if (dH) {
-            const dim3 seg_grid(w.n_seg, s.B);
-            prof.begin(0);
-            hipLaunchKernelGGL(bwd_count_kernel, seg_grid, dim3(256), sizeof(int) * s.S, st, dY, Y, I, cnt, s.S, s.V, w.n_seg, w.seg_len);
-            prof.end(0);
-            if ((r = launch_status()) != LSR_OK) return r;
-            prof.begin(1);
-            hipLaunchKernelGGL(bwd_scan_kernel, dim3(s.B), dim3(256), sizeof(int) * (s.S + 256), st, cnt, bstart, s.S, w.n_seg);
-            prof.end(1);
-            if ((r = launch_status()) != LSR_OK) return r;
-            prof.begin(2);
-            if (L.staged_place)
-                hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
-                                   dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
-            else
-                hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
-                                   s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
-            prof.end(2);
-            if ((r = launch_status()) != LSR_OK) return r;
-            prof.begin(3);
-            if (L.dh_sliced) {
-                // column-sliced gathers, one launch per vocabulary chunk: the rows of W in use stay in L2
-                const int* bounds = bstart;
-                if (w.n_vc > 1) {
-                    int* cb = reinterpret_cast<int*>(base + w.cb_off);
-                    const long long n = (long long)s.B * s.S * (w.n_vc + 1);
-                    hipLaunchKernelGGL(bwd_chunk_bounds_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bstart, perm, cb,
-                                       s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
-                    bounds = cb;
-                }
-                const int bpw = L.bpw, n_groups = L.dh_groups;
-                const dim3 grid((unsigned)n_groups * (unsigned)(s.D / DWS_COLS));
-                for (int vc = 0; vc < w.n_vc; ++vc) {
-#define LSR_DH(T, BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW>), grid, dim3(256), 0, st, static_cast<const T*>(W), bounds, \
-                                          perm, dH, s.B, s.S, s.D, s.V, n_groups, w.n_vc, vc)
-                    if (s.dtype == LSR_F32) {
-                        if (bpw == 1) LSR_DH(float, 1); else if (bpw == 2) LSR_DH(float, 2); else LSR_DH(float, 4);
-                    } else {
-                        if (bpw == 1) LSR_DH(uint16_t, 1); else if (bpw == 2) LSR_DH(uint16_t, 2);
-                        else if (bpw == 4) LSR_DH(uint16_t, 4); else LSR_DH(uint16_t, 8);
-                    }
-#undef LSR_DH
-                }
-            } else {
-                const dim3 grid(s.B, s.S);
-                if (s.dtype == LSR_F32) launch_dh<float>(L.cpt, grid, st, static_cast<const float*>(W), bstart, perm, dH, s.S, s.D, s.V);
-                else launch_dh<uint16_t>(L.cpt, grid, st, static_cast<const uint16_t*>(W), bstart, perm, dH, s.S, s.D, s.V);
-            }
-            prof.end(3);
-            if ((r = launch_status()) != LSR_OK) return r;
-        }
-        if (dW || db) {
-            prof.begin(4);
-            const int VT = L.dw_vt;
-            if (L.dw_sliced) {
-                // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
-                // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
-                const int waves = 4;
-                const int bc = L.dw_bc;                            // sequences per launch
-                const size_t lds = (size_t)bc * VT * 8;
-                const int n_vtiles = L.dw_vtiles, NDC = L.dw_ndc;
-                const dim3 grid((unsigned)n_vtiles * (unsigned)L.dw_slice_groups), block(64 * waves);
-#define LSR_DW(T, C) hipLaunchKernelGGL((bwd_dw_sliced_kernel<T, C>), grid, block, lds, st_dw, static_cast<const T*>(H), dY, Y, I, \
-                                       dW, db, b0, nb, b0 > 0 ? 1 : 0, s.S, s.D, s.V, VT, n_vtiles, NDC)
-                for (int b0 = 0; b0 < s.B; b0 += bc) {
-                    const int nb = s.B - b0 < bc ? s.B - b0 : bc;
-                    // tiles of 16 rows (more than 192 sequences per launch) compact their columns to the non-zero gradients first
-                    if (s.dtype == LSR_F32) { if (VT < 32) LSR_DW(float, true); else LSR_DW(float, false); }
-                    else { if (VT < 32) LSR_DW(uint16_t, true); else LSR_DW(uint16_t, false); }
-                }
-#undef LSR_DW
-            } else {
-                const size_t lds = (size_t)s.B * VT * 8;
-                const dim3 grid(L.dw_vtiles);
-                if (s.dtype == LSR_F32) launch_dw<float>(L.cpt, grid, lds, st_dw, static_cast<const float*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
-                else launch_dw<uint16_t>(L.cpt, grid, lds, st_dw, static_cast<const uint16_t*>(H), dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT);
-            }
-            prof.end(4);
-            if ((r = launch_status()) != LSR_OK) return r;
-        }
-        return LSR_OK;
-    }();
+    if (s.dtype == LSR_F32)
+        rc = backward_launches<float, float>(s, w, L, static_cast<const float*>(H), static_cast<const float*>(W), dY, Y, I,
+                                             static_cast<float*>(dH), static_cast<float*>(dW), db, accumulate, base, st, st_dw, prof);
+    else if (!bf16_out)
+        rc = backward_launches<uint16_t, float>(s, w, L, static_cast<const uint16_t*>(H), static_cast<const uint16_t*>(W), dY, Y, I,
+                                                static_cast<float*>(dH), static_cast<float*>(dW), db, accumulate, base, st, st_dw, prof);
+    else
+        rc = backward_launches<uint16_t, uint16_t>(s, w, L, static_cast<const uint16_t*>(H), static_cast<const uint16_t*>(W), dY, Y, I,
+                                                   static_cast<uint16_t*>(dH), static_cast<uint16_t*>(dW), db, accumulate, base, st,
+                                                   st_dw, prof);
     const int rj = lane.join();
     return rc != LSR_OK ? rc : rj;
+}
+
+template <typename T, typename OT>
+int backward_launches(const Shape& s, const BwdWs& w, const BwdLaunch& L, const T* H, const T* W, const float* dY, const float* Y,
+                      const int32_t* I, OT* dH, OT* dW, float* db, int accumulate, char* base, hipStream_t st, hipStream_t st_dw,
+                      Prof& prof) {
+    constexpr bool OUT_F32 = sizeof(OT) == 4;
+    uint2* perm = reinterpret_cast<uint2*>(base + w.perm_off);
+    int* cnt = reinterpret_cast<int*>(base + w.cnt_off);
+    int* bstart = reinterpret_cast<int*>(base + w.bs_off);
+    int r;
+    if (dH) {
+        const dim3 seg_grid(w.n_seg, s.B);
+        prof.begin(0);
+        hipLaunchKernelGGL(bwd_count_kernel, seg_grid, dim3(256), sizeof(int) * s.S, st, dY, Y, I, cnt, s.S, s.V, w.n_seg, w.seg_len);
+        prof.end(0);
+        if ((r = launch_status()) != LSR_OK) return r;
+        prof.begin(1);
+        hipLaunchKernelGGL(bwd_scan_kernel, dim3(s.B), dim3(256), sizeof(int) * (s.S + 256), st, cnt, bstart, s.S, w.n_seg);
+        prof.end(1);
+        if ((r = launch_status()) != LSR_OK) return r;
+        prof.begin(2);
+        if (L.staged_place)
+            hipLaunchKernelGGL(bwd_place_staged_kernel, seg_grid, dim3(256), sizeof(int) * 2 * s.S + sizeof(uint2) * w.seg_len, st,
+                               dY, Y, I, cnt, bstart, perm, s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+        else
+            hipLaunchKernelGGL(bwd_place_kernel, seg_grid, dim3(64), sizeof(int) * s.S, st, dY, Y, I, cnt, bstart, perm,
+                               s.S, s.V, w.n_seg, w.seg_len, w.key_bits);
+        prof.end(2);
+        if ((r = launch_status()) != LSR_OK) return r;
+        prof.begin(3);
+        if (L.dh_sliced) {
+            // column-sliced gathers, one launch per vocabulary chunk: the rows of W in use stay in L2
+            const int* bounds = bstart;
+            if (w.n_vc > 1) {
+                int* cb = reinterpret_cast<int*>(base + w.cb_off);
+                const long long n = (long long)s.B * s.S * (w.n_vc + 1);
+                hipLaunchKernelGGL(bwd_chunk_bounds_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, bstart, perm, cb,
+                                   s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
+                bounds = cb;
+            }
+            const dim3 grid((unsigned)L.dh_groups * (unsigned)(s.D / DWS_COLS));
+            float* stage = reinterpret_cast<float*>(base + w.dh_stage_off);
+            for (int vc = 0; vc < w.n_vc; ++vc) {
+                const bool last = vc + 1 == w.n_vc;
+                if (OUT_F32) {
+                    // partial sums live in dH itself; the first chunk of a fresh result writes every bucket
+                    float* d = reinterpret_cast<float*>(dH);
+                    const bool fresh = vc == 0 && !accumulate;
+                    launch_dh_sliced<T, float>(L.bpw, grid, st, W, bounds, perm, fresh ? nullptr : d, d, 0, fresh ? 1 : 0, s, L.dh_groups,
+                                               w.n_vc, vc);
+                } else if (w.n_vc == 1) {
+                    launch_dh_sliced<T, OT>(L.bpw, grid, st, W, bounds, perm, nullptr, dH, accumulate, accumulate ? 0 : 1, s, L.dh_groups,
+                                            w.n_vc, vc);
+                } else if (!last) {
+                    launch_dh_sliced<T, float>(L.bpw, grid, st, W, bounds, perm, vc > 0 ? stage : nullptr, stage, 0, vc == 0 ? 1 : 0, s,
+                                               L.dh_groups, w.n_vc, vc);
+                } else {
+                    launch_dh_sliced<T, OT>(L.bpw, grid, st, W, bounds, perm, stage, dH, accumulate, 1, s, L.dh_groups, w.n_vc, vc);
+                }
+            }
+        } else {
+            launch_dh<T, OT>(L.cpt, dim3(s.B, s.S), st, W, bstart, perm, dH, s.S, s.D, s.V, accumulate);
+        }
+        prof.end(3);
+        if ((r = launch_status()) != LSR_OK) return r;
+    }
+    if (dW || db) {
+        prof.begin(4);
+        const int VT = L.dw_vt;
+        if (L.dw_sliced) {
+            // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
+            // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
+            const int waves = 4;
+            const int bc = L.dw_bc;                            // sequences per launch
+            const size_t lds = (size_t)bc * VT * 8;
+            const dim3 grid((unsigned)L.dw_vtiles * (unsigned)L.dw_slice_groups), block(64 * waves);
+            float* stage = reinterpret_cast<float*>(base + w.dw_stage_off);
+            const bool compact = VT < 32;      // tiles of 16 rows (more than 192 sequences per launch) compact their columns first
+            for (int b0 = 0; b0 < s.B; b0 += bc) {
+                const int nb = s.B - b0 < bc ? s.B - b0 : bc;
+                const bool first = b0 == 0, last = b0 + bc >= s.B;
+                const int add_db = (!first || accumulate) ? 1 : 0;
+                if (OUT_F32) {
+                    float* d = reinterpret_cast<float*>(dW);
+                    launch_dw_sliced<T, float>(compact, grid, block, lds, st_dw, H, dY, Y, I, (!first || accumulate) ? d : nullptr, d, 0, db,
+                                               add_db, b0, nb, s, VT, L.dw_vtiles, L.dw_ndc);
+                } else if (first && last) {
+                    launch_dw_sliced<T, OT>(compact, grid, block, lds, st_dw, H, dY, Y, I, nullptr, dW, accumulate, db, add_db, b0, nb, s, VT,
+                                            L.dw_vtiles, L.dw_ndc);
+                } else if (!last) {
+                    launch_dw_sliced<T, float>(compact, grid, block, lds, st_dw, H, dY, Y, I, first ? nullptr : stage, dW ? stage : nullptr, 0,
+                                               db, add_db, b0, nb, s, VT, L.dw_vtiles, L.dw_ndc);
+                } else {
+                    launch_dw_sliced<T, OT>(compact, grid, block, lds, st_dw, H, dY, Y, I, stage, dW, accumulate, db, add_db, b0, nb, s, VT,
+                                            L.dw_vtiles, L.dw_ndc);
+                }
+            }
+        } else {
+            const size_t lds = (size_t)s.B * VT * 8;
+            launch_dw<T, OT>(L.cpt, dim3(L.dw_vtiles), lds, st_dw, H, dY, Y, I, dW, db, s.B, s.S, s.D, s.V, VT, accumulate);
+        }
+        prof.end(4);
+        if ((r = launch_status()) != LSR_OK) return r;
+    }
+    return LSR_OK;
 }
 
 // Runs `launch` `launches` times on st and returns the duration of the last one in ms (< 0 on error).
@@ -662,7 +734,22 @@ int lsr_head_backward(const lsr_head_desc* desc, const void* H, const void* W, c
                       const int32_t* I, float* dH, float* dW, float* db, void* workspace, size_t workspace_bytes,
                       lsr_stream_t stream) {
     Prof prof;
-    return backward_impl(desc, H, W, dY, Y, I, dH, dW, db, workspace, workspace_bytes, stream, prof);
+    return backward_impl(desc, H, W, dY, Y, I, dH, dW, db, nullptr, workspace, workspace_bytes, stream, prof);
+}
+
+size_t lsr_head_backward_ex_workspace_bytes(const lsr_head_desc* desc, const lsr_backward_opts* opts) {
+    Shape s;
+    if (check_desc(desc, &s) != LSR_OK) return 0;
+    const int grad_dtype = opts ? opts->grad_dtype : LSR_F32;
+    if (grad_dtype != LSR_F32 && !(grad_dtype == LSR_BF16 && s.dtype == LSR_BF16)) return 0;
+    return bwd_ws(s, grad_dtype == LSR_BF16).total;
+}
+
+int lsr_head_backward_ex(const lsr_head_desc* desc, const void* H, const void* W, const float* dY, const float* Y,
+                         const int32_t* I, void* dH, void* dW, float* db, const lsr_backward_opts* opts, void* workspace,
+                         size_t workspace_bytes, lsr_stream_t stream) {
+    Prof prof;
+    return backward_impl(desc, H, W, dY, Y, I, dH, dW, db, opts, workspace, workspace_bytes, stream, prof);
 }
 
 int lsr_head_forward_profiled(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
@@ -682,7 +769,7 @@ int lsr_head_backward_profiled(const lsr_head_desc* desc, const void* H, const v
     if (!kernel_ms) return LSR_ERR_NULL;
     Prof prof;
     prof.on = true;
-    const int rc = backward_impl(desc, H, W, dY, Y, I, dH, dW, db, workspace, workspace_bytes, stream, prof);
+    const int rc = backward_impl(desc, H, W, dY, Y, I, dH, dW, db, nullptr, workspace, workspace_bytes, stream, prof);
     const int rc2 = prof.finish(kernel_ms);
     return rc != LSR_OK ? rc : rc2;
 }

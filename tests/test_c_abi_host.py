@@ -111,6 +111,26 @@ def test_backward_argument_errors(lib):
     assert e.value.status == 2
 
 
+def test_backward_options(lib):
+    shape = (2, 16, 64, 70000, lsr.LSR_BF16)
+    base = binding.lsr_head_workspace_bytes(*shape, True)
+    assert binding.lsr_head_backward_ex_workspace_bytes(*shape, lsr.LSR_F32, False) == base
+    assert binding.lsr_head_backward_ex_workspace_bytes(*shape, lsr.LSR_F32, True) == base
+    # bfloat16 dH over several vocabulary chunks keeps float32 partial sums: B*S*D*4 more
+    staged = binding.lsr_head_backward_ex_workspace_bytes(*shape, lsr.LSR_BF16, False)
+    assert base + 2 * 16 * 64 * 4 <= staged <= base + 2 * 16 * 64 * 4 + 256
+    # bfloat16 gradients need bfloat16 parameters; unknown dtypes are refused
+    assert binding.lsr_head_backward_ex_workspace_bytes(2, 16, 64, 1000, lsr.LSR_F32, lsr.LSR_BF16, False) == 0
+    assert binding.lsr_head_backward_ex_workspace_bytes(*shape, 9, False) == 0
+    good = [4096] * 8
+    with pytest.raises(lsr.LsrError) as e:
+        binding.lsr_head_backward_ex(2, 16, 64, 1000, lsr.LSR_F32, *good, lsr.LSR_BF16, False, (4096, 1 << 30), stream=0)
+    assert e.value.status == 3
+    with pytest.raises(lsr.LsrError) as e:
+        binding.lsr_head_backward_ex(*shape, *good, lsr.LSR_BF16, False, (4096, base), stream=0)
+    assert e.value.status == 5          # the staged variant needs the larger workspace
+
+
 def test_profiled_variants_need_a_host_array(lib):
     d = binding._desc(2, 16, 64, 1000, 0)
     rc = lib.lsr_head_forward_profiled(ctypes.byref(d), 4096, 4096, 4096, 4096, 4096, None, 4096, 1 << 30, None, None)

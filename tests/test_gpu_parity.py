@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2603_25011_amd import binding as lsr
 from paper_2603_25011_amd import inputs as wl
 from paper_2603_25011_amd.harness import DeviceHead
 from tests import parity
@@ -199,7 +200,7 @@ def test_autograd_wrapper_matches_direct_calls():
     print(parity.compare_forward(inp, Y.detach().cpu().numpy(), I_np)[3])
     print(parity.compare_backward(inp, I_np, H.grad.float().cpu().numpy(), W.grad.float().cpu().numpy(),
                                   bias.grad.cpu().numpy(), bf16_grads=True))
-    # same kernels, same order: float32 results are identical before the cast to the parameter dtype
+    # same kernels, same order of the float32 sums; the library rounds to the parameter dtype as torch does
     assert torch.equal(H.grad, head.dH.to(torch.bfloat16))
     assert torch.equal(W.grad, head.dW.to(torch.bfloat16))
     assert torch.equal(bias.grad, head.db)
@@ -247,6 +248,70 @@ def test_random_shapes_batched_long_and_wide():
         mask = wl.scattered_mask(rng, B, S, keep=keep)
         print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep}", flush=True)
         run_case(inp, mask=mask)
+
+
+@pytest.mark.parametrize("B,S,D,V,len_lo", [
+    (5, 70, 128, 640, 3),          # one launch each
+    (2, 16, 128, 70000, 1),        # dH over three vocabulary chunks: float32 partial sums staged in the workspace
+    (260, 256, 64, 4100, 60),      # dW over three launches of sequences: staged likewise
+    (3, 40, 200, 900, 1),          # D not a multiple of 64: whole-row kernels
+    (450, 12, 64, 700, 1),         # whole-row dW beside sliced dH
+])
+def test_bf16_gradient_outputs_and_accumulation(B, S, D, V, len_lo):
+    """lsr_head_backward_ex: bfloat16 dH / dW (compared with the oracle within one bf16 step), and
+    accumulation into the caller's buffers for float32 and bfloat16 outputs."""
+    from oracle import lsr_head_oracle as orc
+    inp = wl.make_custom(B, S, D, V, seed=900 + B, len_lo=len_lo)
+    head = DeviceHead(inp)
+    head.forward()
+    head.backward()
+    torch.cuda.synchronize()
+    shape = (head.B, head.S, head.D, head.V, head.dt)
+    dev = head.dev
+    I = head.I.cpu().numpy()
+    parity.compare_forward(inp, head.Y.cpu().numpy(), I)
+    dH_ref, dW_ref, db_ref, _, _ = orc.backward(inp.H, inp.W, inp.bias, inp.mask, inp.dY, I_override=I)
+    f32 = (head.dH.clone(), head.dW.clone(), head.db.clone())
+
+    def run(grad_dtype, accumulate, dH, dW, db):
+        ws = torch.empty(lsr.lsr_head_backward_ex_workspace_bytes(*shape, grad_dtype, accumulate), dtype=torch.uint8, device=dev)
+        lsr.lsr_head_backward_ex(*shape, head.H, head.W, head.dY, head.Y, head.I, dH, dW, db, grad_dtype, accumulate, ws)
+        torch.cuda.synchronize()
+
+    # float32, overwrite: the same launches as lsr_head_backward
+    out = [torch.full_like(t, float("nan")) for t in f32]
+    run(lsr.LSR_F32, False, *out)
+    for a, b_ in zip(out, f32):
+        assert torch.equal(a, b_)
+    # bfloat16, overwrite
+    dH16 = torch.full((B, S, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    dW16 = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    db32 = torch.full((V,), float("nan"), device=dev)
+    run(lsr.LSR_BF16, False, dH16, dW16, db32)
+    parity.check_close_bf16("dH bf16", dH16.float().cpu().numpy(), dH_ref)
+    parity.check_close_bf16("dW bf16", dW16.float().cpu().numpy(), dW_ref)
+    assert torch.equal(db32, f32[2])
+    # one rounding of the float32 result, exactly
+    assert torch.equal(dH16, f32[0].to(torch.bfloat16)) and torch.equal(dW16, f32[1].to(torch.bfloat16))
+    # float32, accumulate into buffers that already hold something
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    base = [torch.randn(t.shape, device=dev, generator=g) for t in f32]
+    out = [t.clone() for t in base]
+    run(lsr.LSR_F32, True, *out)
+    for name, a, b0, ref in zip(("dH", "dW", "db"), out, base, (dH_ref, dW_ref, db_ref)):
+        parity.check_close(name + " accumulated", a.cpu().numpy(), b0.cpu().numpy().astype(np.float64) + ref)
+    # bfloat16, accumulate
+    b16 = [base[0].to(torch.bfloat16), base[1].to(torch.bfloat16)]
+    dH16, dW16, db32 = b16[0].clone(), b16[1].clone(), base[2].clone()
+    run(lsr.LSR_BF16, True, dH16, dW16, db32)
+    parity.check_close_bf16("dH bf16 accumulated", dH16.float().cpu().numpy(), b16[0].float().cpu().numpy().astype(np.float64) + dH_ref)
+    parity.check_close_bf16("dW bf16 accumulated", dW16.float().cpu().numpy(), b16[1].float().cpu().numpy().astype(np.float64) + dW_ref)
+    parity.check_close("db accumulated", db32.cpu().numpy(), base[2].cpu().numpy().astype(np.float64) + db_ref)
+    # subsets of outputs
+    dW16b = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    run(lsr.LSR_BF16, False, None, dW16b, None)
+    assert torch.equal(dW16b, f32[1].to(torch.bfloat16))
 
 
 def test_two_host_threads_on_two_streams():
