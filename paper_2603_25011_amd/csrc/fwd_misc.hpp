@@ -44,14 +44,14 @@ __global__ __launch_bounds__(PREP_THREADS) void fwd_prep_kernel(const uint8_t* _
     if (tid == 0) len[b] = base;
 }
 
-// Packing plan for the MFMA forward.  Every sequence takes ceil(len / 32) blocks of 32 rows (one
-// block if it has no valid token, so that its zero output is still written); blk0 is the exclusive
-// prefix sum of the block counts and blk0[B] the length of the block list.  One workgroup; B is small
-// next to the GEMM.
+// Packing plan for the MFMA forward.  Every sequence takes ceil(len / seg) segments of seg rows (one
+// segment if it has no valid token, so that its zero output is still written; seg = 32, or 8 for batches
+// of short sequences); seg0 is the exclusive prefix sum of the segment counts and seg0[B] the length of
+// the segment list.  One workgroup; B is small next to the GEMM.
 constexpr int PLAN_THREADS = 256;
 
 __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __restrict__ len, int* __restrict__ blk0,
-                                                                 int B) {
+                                                                 int B, int seg) {
     __shared__ int s_scan[PLAN_THREADS];
     const int tid = threadIdx.x;
     int base = 0;
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
         const int b = b0 + tid;
         int n = 0;
         if (b < B) {
-            n = (len[b] + 31) >> 5;
+            n = (len[b] + seg - 1) / seg;
             n = n > 0 ? n : 1;
         }
         s_scan[tid] = n;
@@ -78,23 +78,23 @@ __global__ __launch_bounds__(PLAN_THREADS) void fwd_plan_kernel(const int* __res
 }
 
 // Row table of the packed layout, one workgroup per sequence: packed row k of the sequence reads
-// token pos[min(k, len-1)] (the tail of the last block repeats the last valid token), and every
-// block records its sequence and whether it begins it, ends it, and whether the sequence is empty.
+// token pos[min(k, len-1)] (the tail of the last segment repeats the last valid token), and every
+// segment records its sequence and whether it begins it, ends it, and whether the sequence is empty.
 constexpr int FWD_ROWS_THREADS = 256;
 
 __global__ __launch_bounds__(FWD_ROWS_THREADS) void fwd_rows_kernel(const int* __restrict__ len,
                                                                      const int* __restrict__ pos,
                                                                      const int* __restrict__ blk0,
                                                                      int2* __restrict__ rows,
-                                                                     int* __restrict__ blk_meta, int S) {
+                                                                     int* __restrict__ blk_meta, int S, int seg) {
     const int b = blockIdx.x;
     const int n = len[b];
     const int g0 = blk0[b];
     const int nblk = blk0[b + 1] - g0;
     const int* prow = pos + (size_t)b * S;
-    for (int k = threadIdx.x; k < nblk * 32; k += FWD_ROWS_THREADS) {
+    for (int k = threadIdx.x; k < nblk * seg; k += FWD_ROWS_THREADS) {
         const int s = n > 0 ? prow[k < n ? k : n - 1] : 0;
-        rows[(size_t)g0 * 32 + k] = make_int2(b * S + s, s);
+        rows[(size_t)g0 * seg + k] = make_int2(b * S + s, s);
     }
     for (int k = threadIdx.x; k < nblk; k += FWD_ROWS_THREADS)
         blk_meta[g0 + k] = b | (k == nblk - 1 ? FWD_META_LAST : 0) | (n == 0 ? FWD_META_EMPTY : 0) |
@@ -115,7 +115,7 @@ constexpr int PACK_MAX_TOKENS = 16384;
 __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* __restrict__ mask, int* __restrict__ len,
                                                                  int* __restrict__ pos, int* __restrict__ blk0,
                                                                  int2* __restrict__ rows, int* __restrict__ blk_meta,
-                                                                 int B, int S) {
+                                                                 int B, int S, int seg) {
     __shared__ int s_len[PACK_MAX_B];
     __shared__ int s_blk0[PACK_MAX_B + 1];
     __shared__ int s_part[PACK_THREADS];
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* _
     const int per = (B + PACK_THREADS - 1) / PACK_THREADS;
     const int lo = min(B, tid * per), hi = min(B, lo + per);
     int sum = 0;
-    for (int b = lo; b < hi; ++b) sum += max(1, (s_len[b] + 31) >> 5);
+    for (int b = lo; b < hi; ++b) sum += max(1, (s_len[b] + seg - 1) / seg);
     s_part[tid] = sum;
     __syncthreads();
     for (int off = 1; off < PACK_THREADS; off <<= 1) {
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* _
     for (int b = lo; b < hi; ++b) {
         s_blk0[b] = run;
         blk0[b] = run;
-        run += max(1, (s_len[b] + 31) >> 5);
+        run += max(1, (s_len[b] + seg - 1) / seg);
     }
     if (tid == PACK_THREADS - 1) { s_blk0[B] = s_part[tid]; blk0[B] = s_part[tid]; }
     __syncthreads();
@@ -163,9 +163,9 @@ __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* _
         const int g0 = s_blk0[b];
         const int nblk = s_blk0[b + 1] - g0;
         const int* prow = pos + (size_t)b * S;
-        for (int k = lane; k < nblk * 32; k += 64) {
+        for (int k = lane; k < nblk * seg; k += 64) {
             const int s = n > 0 ? prow[k < n ? k : n - 1] : 0;
-            rows[(size_t)g0 * 32 + k] = make_int2(b * S + s, s);
+            rows[(size_t)g0 * seg + k] = make_int2(b * S + s, s);
         }
         for (int k = lane; k < nblk; k += 64)
             blk_meta[g0 + k] = b | (k == nblk - 1 ? FWD_META_LAST : 0) | (n == 0 ? FWD_META_EMPTY : 0) |
@@ -180,7 +180,8 @@ __global__ __launch_bounds__(PACK_THREADS) void fwd_pack_kernel(const uint8_t* _
 // pieces in order (later pieces hold higher positions, so an equal maximum keeps the earlier
 // position), applies bias, ReLU and log1p (F4) and overwrites Y and I with the final values.
 // grid (ceil(V/256), up to FWD_MERGE_ROWS): a workgroup walks the chunks y, y + gridDim.y, ... (most end
-// with a whole sequence and cost one table read).  tpc = most tiles per chunk (ChunkSplit).
+// with a whole sequence and cost one table read).  tpc = most tiles per chunk, spt = segments per tile
+// (ChunkSplit); blk0 and blk_meta are the segment tables.
 constexpr int FWD_MERGE_THREADS = 256;
 constexpr int FWD_MERGE_ROWS = 4;
 
@@ -191,18 +192,18 @@ __global__ __launch_bounds__(FWD_MERGE_THREADS) void fwd_merge_kernel(const int*
                                                                        const int* __restrict__ part_s,
                                                                        const float* __restrict__ bias,
                                                                        float* __restrict__ Y, int* __restrict__ I,
-                                                                       int B, int V, int tpc) {
+                                                                       int B, int V, int tpc, int spt) {
     const int n_blocks = blk0[B];
-    const ChunkSplit cs = chunk_split(n_blocks, tpc);
+    const ChunkSplit cs = chunk_split(n_blocks, tpc, spt);
     const int v = blockIdx.x * FWD_MERGE_THREADS + threadIdx.x;
     for (int c = blockIdx.y; c < cs.nc; c += gridDim.y) {
-        const int c_lo = cs.first_tile(c) * FWD_TB;
-        const int c_hi = min(n_blocks, cs.first_tile(c + 1) * FWD_TB);     // first block behind the chunk
+        const int c_lo = cs.first_tile(c) * spt;
+        const int c_hi = min(n_blocks, cs.first_tile(c + 1) * spt);        // first segment behind the chunk
         const int meta = blk_meta[c_hi - 1];
         if (meta & FWD_META_LAST) continue;                                // the chunk ends with a sequence
         const int b = meta & FWD_META_SEQ;
         if (blk0[b] < c_lo) continue;                                      // began in an earlier chunk: joined from there
-        const int k_end = cs.chunk_of_tile((blk0[b + 1] - 1) / FWD_TB);    // chunk that holds the sequence's last block
+        const int k_end = cs.chunk_of_tile((blk0[b + 1] - 1) / spt);       // chunk that holds the sequence's last segment
         if (v >= V) continue;
         const size_t o = (size_t)b * V + v;
         float m = Y[o];

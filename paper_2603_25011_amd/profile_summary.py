@@ -82,8 +82,6 @@ def main():
     ap.add_argument("prof_dir")
     ap.add_argument("workload")
     ap.add_argument("--write", action="store_true", help="store the summaries under profiles/ and update traffic.json")
-    ap.add_argument("--steps-counted", type=int, default=4,
-                    help="forward+backward steps in the counter runs (warm-up + timed; default 1 + 3)")
     args = ap.parse_args()
     d = args.prof_dir
     out = {}
@@ -115,28 +113,33 @@ def main():
                  "  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/prof/write -o write --output-format csv -- (same command)", "",
                  "Calibration: lsr::copy_probe_kernel copies 1 GiB (1 048 576 KiB read, 1 048 576 KiB written) per launch and reads",
                  "  FETCH_SIZE %.0f -> scale %.3f;  WRITE_SIZE %.0f -> scale %.3f." % (cf, sf, cw, sw), "",
-                 "Per dispatch (counter units are KiB as printed), and GB per forward / backward after scaling",
-                 "(launches per step = dispatches / %d steps):" % args.steps_counted, "",
+                 "Mean per dispatch (counter units are KiB as printed), and GB per forward / backward call after scaling",
+                 "(launches per call = dispatches of the kernel / dispatches of lsr::fwd_bf16_kernel resp. lsr::bwd_count_kernel):", "",
                  "%-32s %9s %14s %14s %10s %10s" % ("kernel", "launches", "FETCH_SIZE", "WRITE_SIZE", "read GB", "write GB")]
         tot = {"fwd": [0.0, 0.0], "bwd": [0.0, 0.0]}
+        calls = {"fwd": float(len(fetch.get("lsr::fwd_bf16_kernel", {}).get("FETCH_SIZE", [])) or 1),
+                 "bwd": float(len(fetch.get("lsr::bwd_count_kernel", {}).get("FETCH_SIZE", [])) or 1)}
         for k in FWD_KERNELS + BWD_KERNELS:
             f, w = fetch.get(k, {}).get("FETCH_SIZE", []), write.get(k, {}).get("WRITE_SIZE", [])
             if not f and not w:
                 continue
-            per_step = max(len(f), len(w)) / float(args.steps_counted)
+            per_step = max(len(f), len(w)) / calls["fwd" if k in FWD_KERNELS else "bwd"]
             rgb = mean(f) * sf * 1024 * per_step / 1e9
             wgb = mean(w) * sw * 1024 * per_step / 1e9
             lines.append("%-32s %9.2f %14.0f %14.0f %10.3f %10.3f" % (k, per_step, mean(f), mean(w), rgb, wgb))
             side = "fwd" if k in FWD_KERNELS else "bwd"
             tot[side][0] += rgb
             tot[side][1] += wgb
+            if k == "lsr::fwd_bf16_kernel":
+                traffic["fwd_fused_kernel_bytes"] = int((rgb + wgb) * 1e9)
         lines += ["", "forward : %.3f GB read + %.3f GB written per call" % tuple(tot["fwd"]),
                   "backward: %.3f GB read + %.3f GB written per call" % tuple(tot["bwd"])]
         out["hbm_counters"] = "\n".join(lines)
         traffic["fwd_bytes"] = int((tot["fwd"][0] + tot["fwd"][1]) * 1e9)
         traffic["bwd_bytes"] = int((tot["bwd"][0] + tot["bwd"][1]) * 1e9)
         traffic["fetch_scale"], traffic["write_scale"] = sf, sw
-        traffic["source"] = "profiles/%s_hbm_counters.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy)" % args.workload
+        traffic["source"] = ("profiles/%s_hbm_counters.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy)"
+                             % args.workload.split("_")[0])
 
     l2 = counters(os.path.join(d, "l2"))
     if l2:
