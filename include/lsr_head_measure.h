@@ -75,9 +75,10 @@ int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int laun
  *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
  *   [7] rows of the sliced dW gather's staging tile (0: whole-row dW kernel)
  *   [8] sequences per launch of the sliced dW gather (B: one launch)
- *   [9] chunks the forward grid provides for (the longest block list the shape allows)
+ *   [9] chunks the forward grid provides for (the longest token list the shape allows)
+ *   [10] rows per segment of the packed token list (32, or 8 for batches of short sequences)
  */
-#define LSR_PLAN_SLOTS 10
+#define LSR_PLAN_SLOTS 11
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
 
 #ifdef __cplusplus

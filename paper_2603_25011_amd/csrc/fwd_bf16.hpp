@@ -21,12 +21,16 @@
 // Rows are XOR-swizzled inside a slab so that the 16-byte fragment reads are bank-conflict free.
 //
 // Masking and packing.  Only valid tokens are multiplied.  A compaction pass lists the valid
-// positions of every sequence; each sequence is then cut into blocks of 32 rows (the MFMA's row
-// block), the last block padded with repeats of the sequence's last valid token, which cannot change
-// a maximum or its lowest-position arg-max.  The blocks of all sequences form one dense list, and a
-// tile is any 8 consecutive blocks of it, so tiles are full whatever the length mix; a block never
-// mixes two sequences, which keeps the first reduction step (in-lane over a lane's 16 rows of one
-// block) free of masks.
+// positions of every sequence; each sequence is then cut into segments of SEG rows, the last segment
+// padded with repeats of the sequence's last valid token, which cannot change a maximum or its
+// lowest-position arg-max.  The segments of all sequences form one dense list, and a tile is any
+// 256 / SEG consecutive segments of it, so tiles are full whatever the length mix; a segment never
+// mixes two sequences, which keeps the first reduction step (in-lane over a lane's rows of one
+// segment) free of masks.  SEG = 32 is the MFMA's row block (a lane then reduces all 16 of its rows of
+// a block); SEG = 8 serves batches of short sequences (S <= 64: a lane reduces its rows in four groups
+// of four, one per segment of the block), where 32-row segments would pad 4..32-token sequences by
+// 75 % and 8-row segments pad them by 16 %, at the price of four times as many (segment, column) pairs
+// through LDS per tile.
 //
 // Chunks.  Tile j is blocks 8j .. 8j+7 of the list, whatever sequences they belong to, so only the
 // very last tile can be short.  The T tiles are split evenly into ceil(T / tpc) chunks of consecutive
@@ -58,24 +62,26 @@ constexpr int fwd_tn(int nwn) { return 64 * nwn; }          // tile columns (voc
 constexpr int fwd_threads(int nwn) { return 128 * nwn; }
 constexpr int FWD_GV_COLS = 1024;  // vocabulary entries per L2-sharing group of tiles
 
-constexpr int FWD_BLK = 32;                      // rows per block
+constexpr int FWD_BLK = 32;                      // rows per MFMA row block
 constexpr int FWD_TB = FWD_TM / FWD_BLK;         // blocks per tile
+constexpr int FWD_SEG_SHORT = 8;                 // rows per segment for batches of short sequences (else FWD_BLK)
+constexpr int FWD_SEG_SHORT_MAX_S = 64;          // sequence lengths up to which the host picks it
 constexpr int FWD_META_LAST = 1 << 31;           // block ends its sequence
 constexpr int FWD_META_EMPTY = 1 << 30;          // the sequence has no valid token
 constexpr int FWD_META_FIRST = 1 << 29;          // block begins its sequence
 constexpr int FWD_META_SEQ = 0xffff;             // sequence index b (B <= 65535)
 
-// The T = ceil(n_blocks / 8) tiles of the block list in nc = ceil(T / tpc) chunks of as equal size as
-// possible: chunk c holds tiles floor(c T / nc) .. floor((c+1) T / nc) - 1.
+// The T = ceil(n_segs / spt) tiles of the segment list (spt segments per tile) in nc = ceil(T / tpc)
+// chunks of as equal size as possible: chunk c holds tiles floor(c T / nc) .. floor((c+1) T / nc) - 1.
 struct ChunkSplit {
     int T, nc;
     __device__ __forceinline__ int first_tile(int c) const { return (int)(((long long)c * T) / nc); }
     // largest c with floor(c T / nc) <= t
     __device__ __forceinline__ int chunk_of_tile(int t) const { return (int)((((long long)t + 1) * nc - 1) / T); }
 };
-__device__ __forceinline__ ChunkSplit chunk_split(int n_blocks, int tpc) {
+__device__ __forceinline__ ChunkSplit chunk_split(int n_segs, int tpc, int spt) {
     ChunkSplit cs;
-    cs.T = (n_blocks + FWD_TB - 1) / FWD_TB;
+    cs.T = (n_segs + spt - 1) / spt;
     cs.nc = (cs.T + tpc - 1) / tpc;
     return cs;
 }
@@ -84,9 +90,9 @@ struct FwdParams {
     const uint16_t* H;
     const uint16_t* W;
     const float* bias;
-    const int2* rows;        // [n_blocks * 32] per packed row: (row of H = b*S + s, position s)
-    const int* blk_meta;     // [n_blocks] sequence index b, ORed with FWD_META_LAST / _EMPTY / _FIRST
-    const int* n_blocks;     // length of the block list (written by the planning pass)
+    const int2* rows;        // [n_segs * SEG] per packed row: (row of H = b*S + s, position s)
+    const int* blk_meta;     // [n_segs] sequence index b, ORed with FWD_META_LAST / _EMPTY / _FIRST
+    const int* n_blocks;     // n_segs: length of the segment list (written by the planning pass)
     float* Y;
     int* I;                  // may be null
     float* part_m;           // [n_chunks][V] pieces of sequences that begin in an earlier chunk
@@ -256,11 +262,16 @@ __device__ __forceinline__ void wait_vmcnt() {
 //   ARG  track the arg-max position (I requested)
 //   DMA  operands go global -> LDS directly (D a multiple of 64, H and W below 4 GiB each); otherwise
 //        through registers, with 64-bit addresses and a zero-filled last slab
+//   SEG  rows per segment of the packed token list: 32 (FWD_BLK) or 8 (FWD_SEG_SHORT)
 // (Built and measured slower, and not kept as parameters: two 4-wave workgroups per CU on 256 x 128
 //  tiles, which move 1.5x the bytes into LDS, -20 %; 32-deep slabs in four stages, -6 %.)
 constexpr int FWD_NWN = 4;               // wave columns
-template <bool ARG, bool DMA>
+template <bool ARG, bool DMA, int SEG>
 __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdParams p) {
+    static_assert(SEG == 32 || SEG == 16 || SEG == 8, "a segment is a whole number of a lane's register quads");
+    constexpr int SPB = FWD_BLK / SEG;       // segments per row block
+    constexpr int SPT = FWD_TM / SEG;        // segments per tile
+    constexpr int RPS = 16 / SPB;            // accumulator registers of a lane per segment
     constexpr int NWN = FWD_NWN;
     constexpr int BK = 64;                   // K elements per slab
     constexpr int NS = 2;                    // ring stages
@@ -278,7 +289,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     constexpr int STAGE = SLAB_A + SLAB_B;
     constexpr int LPT = IPA + IPB;           // loads per thread per slab (A then B)
     constexpr int JSTEP = NW * 1024;         // LDS bytes between a wave's consecutive accesses
-    constexpr int PM_BYTES = FWD_TB * TN * 4;
+    constexpr int PM_BYTES = SPT * TN * 4;   // one float (or int) per (segment, column) of a tile
 
     // One array per ring stage: distinct objects keep the compiler from serialising a fragment read
     // of one stage against traffic into another.
@@ -295,9 +306,12 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     __shared__ __attribute__((aligned(1024))) int2 s_rows[2][FWD_TM];   // (row of H = b*S+s, position s) per tile row
     // blk_meta of each tile block, indexed t % 4: the scan of tile t-1 may still be reading its records
     // when the records of tile t+1 arrive
-    __shared__ __attribute__((aligned(64))) int s_meta[4][16];
-    // per (block, column): max logit of the block and its position
-    __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[2 * PM_BYTES];
+    __shared__ __attribute__((aligned(128))) int s_meta[4][32];
+    // per (segment, column): max logit of the segment and its position.  With 32-row segments the table
+    // (16 KB) has memory of its own; with shorter segments (up to 64 KB) it lies in ring stage 1, which is
+    // free from the last slab's barrier to the first slab barrier of the next tile (see the epilogue).
+    __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[SEG == FWD_BLK ? 2 * PM_BYTES : 16];
+    static_assert(2 * PM_BYTES <= STAGE, "the pair table must fit a ring stage");
 
     // ---- workgroup -> (chunk, vocabulary tile); contiguous logical ranges per XCD ----
     const int per_xcd = gridDim.x >> 3;
@@ -310,12 +324,12 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     const int vt = vg * p.gv + (rem - rc * p.gv);
     if (vt >= p.n_vtiles) return;
     const int v0 = vt * TN;
-    const int n_blocks = *p.n_blocks;
-    const ChunkSplit cs = chunk_split(n_blocks, p.tpc);
+    const int n_segs = *p.n_blocks;
+    const ChunkSplit cs = chunk_split(n_segs, p.tpc, SPT);
     if (rc >= cs.nc) return;                                     // the grid allows for the longest possible list
-    const int gb_lo = cs.first_tile(rc) * FWD_TB;
-    const int nb = min(n_blocks, cs.first_tile(rc + 1) * FWD_TB) - gb_lo;     // blocks of this chunk
-    const int n_tiles = (nb + FWD_TB - 1) / FWD_TB;
+    const int gs_lo = cs.first_tile(rc) * SPT;
+    const int ns = min(n_segs, cs.first_tile(rc + 1) * SPT) - gs_lo;          // segments of this chunk
+    const int n_tiles = (ns + SPT - 1) / SPT;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -361,16 +375,16 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
 
     // ---- row tables of tile t into buffer buf, by direct-to-LDS loads (no registers held while the
     //      tile before it is multiplied): waves 0 and 1 bring 128 rows each (two per lane), wave 2
-    //      the block records.  Rows of dead blocks of a short last tile repeat its last live rows. ----
+    //      the segment records.  Rows of dead segments of a short last tile repeat its last live rows. ----
     auto fetch_rows = [&](int t, int buf) {
-        const int nact_t = min(FWD_TB, nb - FWD_TB * t);
-        const size_t b0 = (size_t)gb_lo + (size_t)FWD_TB * t;
+        const int nseg_t = min(SPT, ns - SPT * t);
+        const size_t g0 = (size_t)gs_lo + (size_t)SPT * t;
         if (wave < 2) {
-            const int r = min(2 * (wave * 64 + lane), nact_t * FWD_BLK - 2);
-            dma16_to_lds(p.rows + b0 * FWD_BLK + r,
+            const int r = min(2 * (wave * 64 + lane), nseg_t * SEG - 2);
+            dma16_to_lds(p.rows + g0 * SEG + r,
                          __builtin_amdgcn_readfirstlane(lds_addr(&s_rows[buf][0]) + wave * 1024));
-        } else if (wave == 2 && lane < nact_t) {
-            dma4_to_lds(p.blk_meta + b0 + lane, __builtin_amdgcn_readfirstlane(lds_addr(&s_meta[t & 3][0])));
+        } else if (wave == 2 && lane < nseg_t) {
+            dma4_to_lds(p.blk_meta + g0 + lane, __builtin_amdgcn_readfirstlane(lds_addr(&s_meta[t & 3][0])));
         }
     };
     fetch_rows(0, 0);
@@ -398,7 +412,8 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     bool prefetched = false;      // the first slab of the coming tile is already in flight
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
-        const int nact = min(FWD_TB, nb - FWD_TB * t);     // live blocks of this tile
+        const int nseg = min(SPT, ns - SPT * t);           // live segments of this tile
+        const int nact = (nseg + SPB - 1) / SPB;           // live blocks
         const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
         const bool has_next = t + 1 < n_tiles;
         // With two stages and an even slab count a tile ends in stage 1, so the first slab of the next
@@ -538,73 +553,91 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
             }
         }
 
-        // ---- epilogue, part 1: every live block of this wave -> one (max, position) per column ----
-        float* s_pm = reinterpret_cast<float*>(&s_pm_own[0]);
-        int* s_ps = reinterpret_cast<int*>(s_pm) + FWD_TB * TN;
+        // ---- epilogue, part 1: every segment of this wave's live blocks -> one (max, position) per column ----
+        uint8_t* pm_base;
+        if constexpr (SEG == FWD_BLK) pm_base = &s_pm_own[0];
+        else if constexpr (DMA) pm_base = &s_ring1[0];
+        else pm_base = &s_pair[1][0];
+        if constexpr (SEG != FWD_BLK && DMA) {
+            // the table lies in ring stage 1.  With an odd slab count the last slab sat in stage 0 and every
+            // read of stage 1 ended before that slab's barrier; with an even count the last slab sat in
+            // stage 1 itself, and every wave has to be past its fragment reads first
+            if ((nk & 1) == 0) __syncthreads();
+        }
+        float* s_pm = reinterpret_cast<float*>(pm_base);
+        int* s_ps = reinterpret_cast<int*>(s_pm) + SPT * TN;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (i < na) {
                 const int blk = 2 * i + wm;
-                float mm[2];
-                int ss[2];
+                float mm[2][SPB];
+                int ss[2][SPB];
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    // rows grow with the register index, and positions with the rows: the first
-                    // register that holds the maximum is the lowest position in this lane
-                    // the maximum by a chain of three-way maxima, then the first register equal to it
-                    float m = acc[i][c][0];
 #pragma unroll
-                    for (int r = 1; r < 15; r += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, acc[i][c][r]), acc[i][c][r + 1]);
-                    m = __builtin_fmaxf(m, acc[i][c][15]);
-                    // e: row of that register within the block, for half-wave 0 (constants per register)
-                    int e = acc_row(0, 15, 0);
-                    if (ARG) {
+                    for (int j = 0; j < SPB; ++j) {
+                        // rows grow with the register index, and positions with the rows: the first
+                        // register that holds the maximum is the lowest position in this lane
+                        // the maximum by a chain of three-way maxima, then the first register equal to it
+                        const int r0 = j * RPS;
+                        float m = acc[i][c][r0];
 #pragma unroll
-                        for (int r = 14; r >= 0; --r) e = acc[i][c][r] == m ? acc_row(0, r, 0) : e;
+                        for (int r = 1; r < RPS - 1; r += 2)
+                            m = __builtin_fmaxf(__builtin_fmaxf(m, acc[i][c][r0 + r]), acc[i][c][r0 + r + 1]);
+                        m = __builtin_fmaxf(m, acc[i][c][r0 + RPS - 1]);
+                        // e: row of that register within the block, for half-wave 0 (constants per register)
+                        int e = acc_row(0, r0 + RPS - 1, 0);
+                        if (ARG) {
+#pragma unroll
+                            for (int r = RPS - 2; r >= 0; --r) e = acc[i][c][r0 + r] == m ? acc_row(0, r0 + r, 0) : e;
+                        }
+                        mm[c][j] = m;
+                        ss[c][j] = ARG ? s_rows[buf][blk * FWD_BLK + half * 4 + e].y : 0;
                     }
-                    mm[c] = m;
-                    ss[c] = ARG ? s_rows[buf][blk * FWD_BLK + half * 4 + e].y : 0;
                 }
                 // Half-wave q stores column 32 q + l32, so it needs the other half-wave's pair for column
                 // block q only.  One swap of the upper half of the c = 0 register with the lower half of
                 // the c = 1 register leaves, in both half-waves, the two candidates of the column the
                 // lane stores (own and partner; which is which does not matter to a symmetric choice).
-                const auto pm = __builtin_amdgcn_permlane32_swap(__float_as_int(mm[0]), __float_as_int(mm[1]), false, false);
-                float m = __int_as_float(pm[0]);
-                const float mo = __int_as_float(pm[1]);
-                int sp = 0;
-                if (ARG) {
-                    const auto ps = __builtin_amdgcn_permlane32_swap(ss[0], ss[1], false, false);
-                    sp = ps[0];
-                    const int so = ps[1];
-                    if (mo > m || (mo == m && so < sp)) sp = so;
+#pragma unroll
+                for (int j = 0; j < SPB; ++j) {
+                    const auto pm = __builtin_amdgcn_permlane32_swap(__float_as_int(mm[0][j]), __float_as_int(mm[1][j]), false, false);
+                    float m = __int_as_float(pm[0]);
+                    const float mo = __int_as_float(pm[1]);
+                    int sp = 0;
+                    if (ARG) {
+                        const auto ps = __builtin_amdgcn_permlane32_swap(ss[0][j], ss[1][j], false, false);
+                        sp = ps[0];
+                        const int so = ps[1];
+                        if (mo > m || (mo == m && so < sp)) sp = so;
+                    }
+                    m = fmaxf(m, mo);
+                    const int col = wn * 64 + half * 32 + l32;
+                    s_pm[(blk * SPB + j) * TN + col] = m;
+                    if (ARG) s_ps[(blk * SPB + j) * TN + col] = sp;
                 }
-                m = fmaxf(m, mo);
-                const int col = wn * 64 + half * 32 + l32;
-                s_pm[blk * TN + col] = m;
-                if (ARG) s_ps[blk * TN + col] = sp;
             }
         }
         if (nk < NS) wait_vmcnt<0>();     // the next tile's tables, if the slab loop was too short to wait for them
         __syncthreads();
         prefetched = pf_next;
-        // ---- part 2: join the blocks of each sequence; finalise (F4) where a sequence ends.  Only
+        // ---- part 2: join the segments of each sequence; finalise (F4) where a sequence ends.  Only
         //      the first TN threads take part; the others go on to the next tile. ----
         if (tid < TN) {
             // all table reads first (the accumulators are dead here, registers are free): the walk over
-            // the blocks is a dependent chain, and the other four waves wait for it at the next barrier
-            float pm[FWD_TB];
-            int ps[FWD_TB], mt[FWD_TB];
+            // the segments is a dependent chain, and the other four waves wait for it at the next barrier
+            float pm[SPT];
+            int ps[SPT], mt[SPT];
 #pragma unroll
-            for (int k = 0; k < FWD_TB; ++k) {
-                const bool live = k < nact;
+            for (int k = 0; k < SPT; ++k) {
+                const bool live = k < nseg;
                 pm[k] = live ? s_pm[k * TN + tid] : -INFINITY;
                 ps[k] = (ARG && live) ? s_ps[k * TN + tid] : 0;
                 mt[k] = live ? s_meta[t & 3][k] : 0;
             }
 #pragma unroll
-            for (int k = 0; k < FWD_TB; ++k) {
-                if (pm[k] > run_m) {              // later blocks hold higher positions: strict
+            for (int k = 0; k < SPT; ++k) {
+                if (pm[k] > run_m) {              // later segments hold higher positions: strict
                     run_m = pm[k];
                     run_s = ps[k];
                 }
@@ -630,7 +663,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
             }
             if (!has_next) {
                 // the chunk may end inside a sequence: leave the open piece for the merge pass
-                const int meta = s_meta[t & 3][nact - 1];
+                const int meta = s_meta[t & 3][nseg - 1];
                 if (!(meta & FWD_META_LAST) && v_out < p.V) {
                     if (head_open) {                        // one sequence covers the whole chunk
                         const size_t o = (size_t)rc * p.V + v_out;

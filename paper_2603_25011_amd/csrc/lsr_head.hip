@@ -55,27 +55,33 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 // 8.78 / 8.95), the kernel then splitting the real tiles evenly over the chunks.  Never more chunks than
 // sequences: the per-chunk slots for cut sequences (8 bytes per vocabulary entry) then stay below the
 // size of the outputs Y and I, whatever the sequence length.
+// Rows per segment of the packed token list: the MFMA row block, or 8 for batches of short sequences
+// (B=256, S=32, lengths 4..32: 8192 packed rows with 32-row segments, 5 400 with 8-row segments).
+int fwd_seg(const Shape& s) { return s.S <= FWD_SEG_SHORT_MAX_S ? FWD_SEG_SHORT : FWD_BLK; }
+
 struct FwdChunks { int tpc, n_chunks; bool cut_possible; };
 FwdChunks fwd_chunks(const Shape& s) {
-    const long blocks_max = (long)s.B * ((s.S + 31) / 32);
-    const long tiles_max = (blocks_max + FWD_TB - 1) / FWD_TB;
+    const int seg = fwd_seg(s);
+    const long segs_max = (long)s.B * ((s.S + seg - 1) / seg);
+    const long tiles_max = (segs_max * seg + FWD_TM - 1) / FWD_TM;
     FwdChunks c;
     c.tpc = 4;
     const long per_seq = (tiles_max + s.B - 1) / s.B;
     if (c.tpc < per_seq) c.tpc = (int)per_seq;
     c.n_chunks = (int)((tiles_max + c.tpc - 1) / c.tpc);
-    // a sequence of one block can never lie across a chunk boundary: no pieces, no merge pass
-    c.cut_possible = s.S > FWD_BLK && c.n_chunks > 1;
+    // a sequence of one segment can never lie across a chunk boundary: no pieces, no merge pass
+    c.cut_possible = s.S > seg && c.n_chunks > 1;
     return c;
 }
 
-// ---- forward workspace: len[B] | pos[B*S] | blk0[B+1] | blk_meta[blocks] | rows[blocks*32] |
-//      part_m[chunks*V] | part_s[chunks*V]; blocks = B * ceil(S/32) being the most the packed layout can
+// ---- forward workspace: len[B] | pos[B*S] | seg0[B+1] | seg_meta[segs] | rows[segs*seg] |
+//      part_m[chunks*V] | part_s[chunks*V]; segs = B * ceil(S/seg) being the most the packed layout can
 //      need, the two part arrays only where a chunk boundary can fall inside a sequence ----
 struct FwdWs { size_t len_off, pos_off, blk0_off, meta_off, rows_off, pm_off, ps_off, total; };
 FwdWs fwd_ws(const Shape& s) {
     FwdWs w;
-    const size_t blocks = (size_t)s.B * ((s.S + 31) / 32);
+    const int seg = fwd_seg(s);
+    const size_t blocks = (size_t)s.B * ((s.S + seg - 1) / seg);          // segments
     const FwdChunks c = fwd_chunks(s);
     const size_t part = (s.dtype == LSR_BF16 && c.cut_possible) ? align_up(sizeof(float) * (size_t)c.n_chunks * s.V) : 0;
     w.len_off = 0;
@@ -83,7 +89,7 @@ FwdWs fwd_ws(const Shape& s) {
     w.blk0_off = w.pos_off + align_up(sizeof(int) * (size_t)s.B * s.S);
     w.meta_off = w.blk0_off + align_up(sizeof(int) * ((size_t)s.B + 1));
     w.rows_off = w.meta_off + align_up(sizeof(int) * blocks);
-    w.pm_off = w.rows_off + align_up(sizeof(int2) * blocks * 32);
+    w.pm_off = w.rows_off + align_up(sizeof(int2) * blocks * seg);
     w.ps_off = w.pm_off + part;
     w.total = w.ps_off + part;
     return w;
@@ -255,21 +261,27 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : L
 // Kernel choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab and H and W are
 // each below 4 GiB (32-bit byte offsets per lane), else the register-staged loader (64-bit addresses,
 // zero-fills the last slab).
-template <bool DMA>
+template <bool DMA, int SEG>
 void launch_fwd_cfg(FwdParams p, int V, bool arg, hipStream_t st) {
     constexpr int TN = fwd_tn(FWD_NWN);
     p.n_vtiles = (V + TN - 1) / TN;
     p.gv = FWD_GV_COLS / TN;
     p.n_logical = (p.n_vtiles + p.gv - 1) / p.gv * p.gv * p.n_chunks;
     const dim3 grid((p.n_logical + 7) / 8 * 8), block(fwd_threads(FWD_NWN));
-    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA>), grid, block, 0, st, p);
-    else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA>), grid, block, 0, st, p);
+    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA, SEG>), grid, block, 0, st, p);
+    else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA, SEG>), grid, block, 0, st, p);
 }
 
-void launch_fwd_bf16(const FwdParams& p, bool arg, hipStream_t st) {
+void launch_fwd_bf16(const FwdParams& p, int seg, bool arg, hipStream_t st) {
     const bool small = (size_t)p.B * p.S * p.D * 2 < ((size_t)1 << 32) && (size_t)p.V * p.D * 2 < ((size_t)1 << 32);
-    if (p.D % 64 == 0 && small) launch_fwd_cfg<true>(p, p.V, arg, st);
-    else launch_fwd_cfg<false>(p, p.V, arg, st);
+    const bool dma = p.D % 64 == 0 && small;
+    if (seg == FWD_BLK) {
+        if (dma) launch_fwd_cfg<true, FWD_BLK>(p, p.V, arg, st);
+        else launch_fwd_cfg<false, FWD_BLK>(p, p.V, arg, st);
+    } else {
+        if (dma) launch_fwd_cfg<true, FWD_SEG_SHORT>(p, p.V, arg, st);
+        else launch_fwd_cfg<false, FWD_SEG_SHORT>(p, p.V, arg, st);
+    }
 }
 
 int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const float* bias,
@@ -302,11 +314,12 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
     float* part_m = reinterpret_cast<float*>(base + w.pm_off);
     int* part_s = reinterpret_cast<int*>(base + w.ps_off);
     const FwdChunks ck = fwd_chunks(s);
+    const int seg = fwd_seg(s);
     if (one_launch) {
-        hipLaunchKernelGGL(fwd_pack_kernel, dim3(1), dim3(PACK_THREADS), 0, st, mask, len, pos, blk0, rows, blk_meta, s.B, s.S);
+        hipLaunchKernelGGL(fwd_pack_kernel, dim3(1), dim3(PACK_THREADS), 0, st, mask, len, pos, blk0, rows, blk_meta, s.B, s.S, seg);
     } else if (s.dtype == LSR_BF16) {
-        hipLaunchKernelGGL(fwd_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, len, blk0, s.B);
-        hipLaunchKernelGGL(fwd_rows_kernel, dim3(s.B), dim3(FWD_ROWS_THREADS), 0, st, len, pos, blk0, rows, blk_meta, s.S);
+        hipLaunchKernelGGL(fwd_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, len, blk0, s.B, seg);
+        hipLaunchKernelGGL(fwd_rows_kernel, dim3(s.B), dim3(FWD_ROWS_THREADS), 0, st, len, pos, blk0, rows, blk_meta, s.S, seg);
     }
     prof.end(0);
     if ((rc = launch_status()) != LSR_OK) return rc;
@@ -326,7 +339,7 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         p.part_m = part_m; p.part_s = part_s;
         p.B = s.B; p.S = s.S; p.D = s.D; p.V = s.V;
         p.n_chunks = ck.n_chunks; p.tpc = ck.tpc;
-        launch_fwd_bf16(p, I != nullptr, st);
+        launch_fwd_bf16(p, seg, I != nullptr, st);
     }
     prof.end(1);
     if (s.dtype == LSR_BF16 && ck.cut_possible) {
@@ -334,9 +347,9 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         prof.begin(2);
         const dim3 grid((s.V + FWD_MERGE_THREADS - 1) / FWD_MERGE_THREADS, ck.n_chunks < FWD_MERGE_ROWS ? ck.n_chunks : FWD_MERGE_ROWS);
         if (I) hipLaunchKernelGGL((fwd_merge_kernel<true>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
-                                  bias, Y, I, s.B, s.V, ck.tpc);
+                                  bias, Y, I, s.B, s.V, ck.tpc, FWD_TM / seg);
         else   hipLaunchKernelGGL((fwd_merge_kernel<false>), grid, dim3(FWD_MERGE_THREADS), 0, st, blk0, blk_meta, part_m, part_s,
-                                  bias, Y, I, s.B, s.V, ck.tpc);
+                                  bias, Y, I, s.B, s.V, ck.tpc, FWD_TM / seg);
         prof.end(2);
     }
     return launch_status();
@@ -863,6 +876,7 @@ int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     plan[7] = dw_tile_rows(s);
     plan[8] = dw_batch_chunk(s);
     plan[9] = fwd_chunks(s).n_chunks;
+    plan[10] = fwd_seg(s);
     return LSR_OK;
 }
 

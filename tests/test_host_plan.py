@@ -20,14 +20,14 @@ def lib():
 
 def test_plans_of_the_benchmark_shapes():
     p = lsr.lsr_head_plan(64, 512, 1024, 250002, lsr.LSR_BF16)          # C5
-    assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
+    assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "fwd_segment_rows": 32, "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
                  "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64,
                  "dw_sequences_per_launch": 64}
     p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
     p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (1, 1, 16)
-    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"]) == (4, 8)
+    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"]) == (4, 8, 8)      # short sequences: 8-row segments
     p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
     assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
     p = lsr.lsr_head_plan(256, 512, 768, 250002, lsr.LSR_BF16)          # a batch whose H slice is 4x L2: four dW launches
@@ -68,15 +68,17 @@ def test_plan_invariants_on_random_shapes():
                 assert (rows == 0) == (nb * 16 * 8 > 48 * 1024)
                 # several launches only where rows of H are reused often, and few enough that re-reading dW stays small
                 assert nb == B or (V >= 16 * S and (B + nb - 1) // nb <= min(16, 1 + B * esize // 32))
-            tiles_max = (B * ((S + 31) // 32) + 7) // 8
+            seg = p["fwd_segment_rows"]
+            assert seg == (8 if S <= 64 else 32)
+            segs = B * ((S + seg - 1) // seg)
+            tiles_max = (segs * seg + 255) // 256
             assert p["fwd_tiles_per_chunk"] >= 1 and p["fwd_chunks"] <= B
             assert (p["fwd_chunks"] - 1) * p["fwd_tiles_per_chunk"] < tiles_max <= p["fwd_chunks"] * p["fwd_tiles_per_chunk"]
             # forward workspace: O(B*S) tables, plus one (max, position) slot per chunk and vocabulary entry
             # where a chunk boundary can fall inside a sequence (bf16 path, S above one block)
             fw = lsr.lsr_head_workspace_bytes(B, S, D, V, dt, False)
-            blocks = B * ((S + 31) // 32)
-            tables = 4 * B + 4 * B * S + 4 * (B + 1) + 4 * blocks + 8 * 32 * blocks
-            parts = 8 * p["fwd_chunks"] * V if (dt == lsr.LSR_BF16 and S > 32 and p["fwd_chunks"] > 1) else 0
+            tables = 4 * B + 4 * B * S + 4 * (B + 1) + 4 * segs + 8 * seg * segs
+            parts = 8 * p["fwd_chunks"] * V if (dt == lsr.LSR_BF16 and S > seg and p["fwd_chunks"] > 1) else 0
             assert tables + parts <= fw <= tables + parts + 8 * 256
             # the backward workspace holds what the plan implies
             need = 8 * B * V + 4 * B * n_seg * S + 4 * B * (S + 1) + (4 * B * S * (c + 1) if c > 1 else 0)
