@@ -102,7 +102,6 @@ struct FwdParams {
     int n_chunks;            // chunks the grid provides for (from the longest block list the shape allows)
     int tpc;                 // most tiles per chunk
     int gv;                  // vocabulary tiles per L2-sharing group
-    int n_logical;           // ceil(n_vtiles / gv) * gv * n_chunks
 };
 
 // Swizzle of the 16-byte chunk index inside a tile row.  A fragment read has lanes 0..31 on 32
@@ -313,23 +312,39 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     __shared__ __attribute__((aligned(16))) uint8_t s_pm_own[SEG == FWD_BLK ? 2 * PM_BYTES : 16];
     static_assert(2 * PM_BYTES <= STAGE, "the pair table must fit a ring stage");
 
-    // ---- workgroup -> (chunk, vocabulary tile); contiguous logical ranges per XCD ----
-    const int per_xcd = gridDim.x >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= p.n_logical) return;
-    const int group_span = p.n_chunks * p.gv;
-    const int vg = logical / group_span;
-    const int rem = logical - vg * group_span;
-    const int rc = rem / p.gv;
-    const int vt = vg * p.gv + (rem - rc * p.gv);
-    if (vt >= p.n_vtiles) return;
-    const int v0 = vt * TN;
+    // ---- schedule.  A unit of work is (chunk, vocabulary tile); units are ordered in groups of gv
+    //      vocabulary tiles x all chunks, so that units next to each other share rows of W and of H.
+    //      Each XCD takes a contiguous range of the units (its L2 then sees gv tiles of W at a time), and
+    //      the workgroups of an XCD (one per CU, resident for the whole launch) deal that range out
+    //      round-robin: workgroup j walks units j, j + n, j + 2n, ... of the range.  Workgroup ids go
+    //      round-robin over the XCDs, so id & 7 is the XCD and id >> 3 the index on it. ----
     const int n_segs = *p.n_blocks;
     const ChunkSplit cs = chunk_split(n_segs, p.tpc, SPT);
-    if (rc >= cs.nc) return;                                     // the grid allows for the longest possible list
-    const int gs_lo = cs.first_tile(rc) * SPT;
-    const int ns = min(n_segs, cs.first_tile(rc + 1) * SPT) - gs_lo;          // segments of this chunk
-    const int n_tiles = (ns + SPT - 1) / SPT;
+    const int span = cs.nc * p.gv;                                       // units per group of vocabulary tiles
+    const long long n_units = (long long)((p.n_vtiles + p.gv - 1) / p.gv) * span;
+    const int n_local = gridDim.x >> 3;
+    const int u_end = (int)(n_units * ((blockIdx.x & 7) + 1) / 8);
+    struct Unit { int u, vt, rc, g0, ns, n_tiles; };
+    // the first unit at or behind u (in steps of n_local) that exists: the last group of vocabulary
+    // tiles may be short
+    auto open_unit = [&](int u, Unit& x) -> bool {
+        for (; u < u_end; u += n_local) {
+            const int vg = u / span;
+            const int rem = u - vg * span;
+            const int rc = rem / p.gv;
+            const int vt = vg * p.gv + (rem - rc * p.gv);
+            if (vt >= p.n_vtiles) continue;
+            x.u = u; x.vt = vt; x.rc = rc;
+            x.g0 = cs.first_tile(rc) * SPT;                                              // first segment of the chunk
+            x.ns = min(n_segs, cs.first_tile(rc + 1) * SPT) - x.g0;                      // its segments
+            x.n_tiles = (x.ns + SPT - 1) / SPT;
+            return true;
+        }
+        return false;
+    };
+    Unit cur;
+    if (!open_unit((int)(n_units * (blockIdx.x & 7) / 8) + (blockIdx.x >> 3), cur)) return;
+    int cur_t = 0;                                                       // tile of the unit
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -351,14 +366,20 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     // 32 bits (the host takes this path only while H and W are each below 4 GiB).
     size_t woff[DMA ? 1 : IPB];
     uint32_t woff32[DMA ? IPB : 1];
+    int w_vt = -1;                                            // vocabulary tile the offsets belong to
+    auto w_offsets = [&](int vt) {
+        if (vt == w_vt) return;
+        w_vt = vt;
 #pragma unroll
-    for (int j = 0; j < IPB; ++j) {
-        int v = v0 + lrow + NW * RPI * j;
-        v = v < p.V ? v : p.V - 1;
-        const size_t o = ((size_t)v * D + gch * 8) * 2;
-        if constexpr (DMA) woff32[j] = (uint32_t)o;
-        else woff[j] = o;
-    }
+        for (int j = 0; j < IPB; ++j) {
+            int v = vt * TN + lrow + NW * RPI * j;
+            v = v < p.V ? v : p.V - 1;
+            const size_t o = ((size_t)v * D + gch * 8) * 2;
+            if constexpr (DMA) woff32[j] = (uint32_t)o;
+            else woff[j] = o;
+        }
+    };
+    w_offsets(cur.vt);
     const char* const Hb = reinterpret_cast<const char*>(p.H);
     const char* const Wb = reinterpret_cast<const char*>(p.W);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(wave * 1024);
@@ -376,28 +397,29 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     // ---- row tables of tile t into buffer buf, by direct-to-LDS loads (no registers held while the
     //      tile before it is multiplied): waves 0 and 1 bring 128 rows each (two per lane), wave 2
     //      the segment records.  Rows of dead segments of a short last tile repeat its last live rows. ----
-    auto fetch_rows = [&](int t, int buf) {
-        const int nseg_t = min(SPT, ns - SPT * t);
-        const size_t g0 = (size_t)gs_lo + (size_t)SPT * t;
+    //      `it` counts the tiles this workgroup has walked: buffer it & 1, record slot it & 3.
+    auto fetch_rows = [&](const Unit& x, int t, int it) {
+        const int nseg_t = min(SPT, x.ns - SPT * t);
+        const size_t g0 = (size_t)x.g0 + (size_t)SPT * t;
         if (wave < 2) {
             const int r = min(2 * (wave * 64 + lane), nseg_t * SEG - 2);
             dma16_to_lds(p.rows + g0 * SEG + r,
-                         __builtin_amdgcn_readfirstlane(lds_addr(&s_rows[buf][0]) + wave * 1024));
+                         __builtin_amdgcn_readfirstlane(lds_addr(&s_rows[it & 1][0]) + wave * 1024));
         } else if (wave == 2 && lane < nseg_t) {
-            dma4_to_lds(p.blk_meta + g0 + lane, __builtin_amdgcn_readfirstlane(lds_addr(&s_meta[t & 3][0])));
+            dma4_to_lds(p.blk_meta + g0 + lane, __builtin_amdgcn_readfirstlane(lds_addr(&s_meta[it & 3][0])));
         }
     };
-    fetch_rows(0, 0);
+    fetch_rows(cur, 0, 0);
     wait_vmcnt<0>();
 
-    // scan state of thread tid < TN (column v0 + tid): running pair of the sequence still open
+    // scan state of thread tid < TN (column of the unit's vocabulary tile): running pair of the sequence
+    // still open; output column and bias follow the unit
     float run_m = -INFINITY;
     int run_s = 0;
-    const int v_out = v0 + tid;
-    const float bias_v = (tid < TN && v_out < p.V) ? p.bias[v_out] : 0.f;
+    int v_out = 0;
+    float bias_v = 0.f;
+    bool head_open = false;
     __syncthreads();
-    // the chunk begins inside a sequence: until that sequence ends, the running pair is a later piece of it
-    bool head_open = !(s_meta[0][0] & FWD_META_FIRST);
 
     size_t hoff[DMA ? 1 : IPA];
     uint32_t hoff32[DMA ? IPA : 1];
@@ -410,18 +432,38 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
         }
     };
     bool prefetched = false;      // the first slab of the coming tile is already in flight
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        const int nseg = min(SPT, ns - SPT * t);           // live segments of this tile
+    for (int it = 0;; ++it) {
+        const int buf = it & 1;
+        const int t = cur_t;
+        const int rc = cur.rc;
+        const int nseg = min(SPT, cur.ns - SPT * t);       // live segments of this tile
         const int nact = (nseg + SPB - 1) / SPB;           // live blocks
         const int na = (nact + 1 - wm) >> 1;               // ... of this wave; the others are not multiplied
-        const bool has_next = t + 1 < n_tiles;
+        const bool unit_ends = t + 1 == cur.n_tiles;
+        // the tile after this one: the next of the unit, or the first of this workgroup's next unit
+        Unit nxt = cur;
+        int nxt_t = t + 1;
+        bool has_next = true;
+        if (unit_ends) {
+            nxt_t = 0;
+            has_next = open_unit(cur.u + n_local, nxt);
+        }
+        if (t == 0 && tid < TN) {
+            // a unit begins: its output columns and bias; and whether its chunk begins inside a sequence
+            // (until that sequence ends, the running pair is a later piece of it)
+            v_out = cur.vt * TN + tid;
+            bias_v = v_out < p.V ? p.bias[v_out] : 0.f;
+            head_open = !(s_meta[it & 3][0] & FWD_META_FIRST);
+        }
         // With two stages and an even slab count a tile ends in stage 1, so the first slab of the next
         // tile can be requested into stage 0 from inside the last slab and flies during the epilogue.
         const bool pf_next = DMA && has_next && nk >= 2 && (nk & 1) == 0;
-        if (!prefetched) row_offsets(buf);
+        if (!prefetched) {
+            row_offsets(buf);
+            w_offsets(cur.vt);
+        }
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
-        if (has_next) fetch_rows(t + 1, buf ^ 1);
+        if (has_next) fetch_rows(nxt, nxt_t, it + 1);
 
         floatx16 acc[4][2];
 #pragma unroll
@@ -498,6 +540,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
                 }
                 if (pf_next) {                                // nk is even: slab nk-1 lives in stage 1
                     row_offsets(buf ^ 1);                     // this tile's are no longer needed
+                    w_offsets(nxt.vt);
                     step(st1, steady, std::true_type{}, nk - 1);
                 }
                 if constexpr (NA > 0) {                       // last k-step of the last slab
@@ -633,7 +676,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
                 const bool live = k < nseg;
                 pm[k] = live ? s_pm[k * TN + tid] : -INFINITY;
                 ps[k] = (ARG && live) ? s_ps[k * TN + tid] : 0;
-                mt[k] = live ? s_meta[t & 3][k] : 0;
+                mt[k] = live ? s_meta[it & 3][k] : 0;
             }
 #pragma unroll
             for (int k = 0; k < SPT; ++k) {
@@ -661,9 +704,9 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
                     run_s = 0;
                 }
             }
-            if (!has_next) {
+            if (unit_ends) {
                 // the chunk may end inside a sequence: leave the open piece for the merge pass
-                const int meta = s_meta[t & 3][nseg - 1];
+                const int meta = s_meta[it & 3][nseg - 1];
                 if (!(meta & FWD_META_LAST) && v_out < p.V) {
                     if (head_open) {                        // one sequence covers the whole chunk
                         const size_t o = (size_t)rc * p.V + v_out;
@@ -675,8 +718,13 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
                         if (ARG) p.I[o] = run_s;
                     }
                 }
+                run_m = -INFINITY;
+                run_s = 0;
             }
         }
+        if (!has_next) break;
+        cur = nxt;
+        cur_t = nxt_t;
     }
 }
 

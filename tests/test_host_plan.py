@@ -27,7 +27,7 @@ def test_plans_of_the_benchmark_shapes():
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
     p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (1, 1, 16)
-    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"]) == (4, 8, 8)      # short sequences: 8-row segments
+    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"]) == (1, 32, 8)     # short sequences: 8-row segments
     p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
     assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
     p = lsr.lsr_head_plan(256, 512, 768, 250002, lsr.LSR_BF16)          # a batch whose H slice is 4x L2: four dW launches
