@@ -32,18 +32,21 @@
 // 75 % and 8-row segments pad them by 16 %, at the price of four times as many (segment, column) pairs
 // through LDS per tile.
 //
-// Chunks.  Tile j is blocks 8j .. 8j+7 of the list, whatever sequences they belong to, so only the
-// very last tile can be short.  The T tiles are split evenly into ceil(T / tpc) chunks of consecutive
-// tiles (ChunkSplit below); a workgroup owns (chunk, vocabulary tile) and walks the chunk's tiles.  Per tile it reduces every block
-// to one (max, position) per column, and a scan over the tile's blocks carries the running pair of the
-// sequence that is still open in registers from block to block and from tile to tile (the streaming
-// reduction of Sec. 3).  The block that ends a sequence triggers bias + ReLU + log1p and the store of
-// Y and I.  A chunk boundary may fall inside a sequence.  The piece in front of the boundary (the
-// sequence began in this chunk) leaves its raw pair in Y and I; a piece behind a boundary (the chunk
-// begins inside the sequence) leaves its pair in slot `chunk` of the part_m / part_s arrays; a small
-// kernel (fwd_merge_kernel) joins the pieces and finalises.  Chunks of whole sequences would need no
-// such pass but end in short tiles, which cost a whole tile's vocabulary side for a fraction of the rows
-// (measured with chunks cut at sequence starts: 7.4 % of the block slots empty at B=64, S=512).
+// Chunks and units.  Tile j is segments j * 256/SEG .. of the list, whatever sequences they belong to, so
+// only the very last tile can be short.  The T tiles are split evenly into ceil(T / tpc) chunks of
+// consecutive tiles (ChunkSplit below).  A unit of work is (chunk, vocabulary tile): the workgroup that
+// takes it walks the chunk's tiles; per tile it reduces every segment to one (max, position) per column,
+// and a scan over the tile's segments carries the running pair of the sequence that is still open in
+// registers from segment to segment and from tile to tile (the streaming reduction of Sec. 3).  The
+// segment that ends a sequence triggers bias + ReLU + log1p and the store of Y and I.  A chunk boundary
+// may fall inside a sequence.  The piece in front of the boundary (the sequence began in this chunk)
+// leaves its raw pair in Y and I; a piece behind a boundary (the chunk begins inside the sequence)
+// leaves its pair in slot `chunk` of the part_m / part_s arrays; a small kernel (fwd_merge_kernel) joins
+// the pieces and finalises.  Chunks of whole sequences would need no such pass but end in short tiles
+// and need the lengths on the host to size.
+// One workgroup per CU stays resident for the whole launch and walks its share of the units (see the
+// schedule at the top of the kernel); the next unit's row table and first slab are prefetched like the
+// next tile's.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -476,7 +479,6 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
         if constexpr (DMA) {
             // Slab kt goes to ring stage kt % NS.  Each wave-wide load fills 1024 contiguous LDS bytes
             // (lane l lands at +16 l); the wave-uniform base goes through M0.
-            // load n (0 .. LPT-1) of slab kt into ring stage ST: first the A rows, then the B rows
             // load n (0 .. LPT-1) of a slab into ring stage ST: first the A rows, then the B rows; hb and wb
             // are the operand bases already advanced to the slab's K offset (wave-uniform, in SGPRs)
             auto issue_one = [&](auto st, const char* hb, const char* wb, int n) {
