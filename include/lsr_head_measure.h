@@ -69,7 +69,7 @@ int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int laun
 /*
  * The launch plan the host derives from a shape alone, for inspection and tests (no device needed,
  * nothing is launched).  Writes LSR_PLAN_SLOTS int32 values to the HOST array `plan`:
- *   [0] tiles per chunk of the packed forward     [1] segments of the bucket sort per sequence
+ *   [0] most tiles per chunk of the packed forward    [1] segments of the bucket sort per sequence
  *   [2] vocabulary entries per sort segment       [3] 1 if the sort places through LDS, else 0
  *   [4] vocabulary chunks of the dH gather        [5] vocabulary entries per chunk
  *   [6] buckets per wave in the sliced dH gather (0: whole-row dH kernel, D not a multiple of 64)
@@ -77,8 +77,9 @@ int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int laun
  *   [8] sequences per launch of the sliced dW gather (B: one launch)
  *   [9] chunks the forward grid provides for (the longest token list the shape allows)
  *   [10] rows per segment of the packed token list (32, or 8 for batches of short sequences)
+ *   [11] 1 if the forward runs one resident workgroup per CU over its units (shallow problems), else 0
  */
-#define LSR_PLAN_SLOTS 11
+#define LSR_PLAN_SLOTS 12
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
 
 #ifdef __cplusplus

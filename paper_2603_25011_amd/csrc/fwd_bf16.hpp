@@ -265,10 +265,12 @@ __device__ __forceinline__ void wait_vmcnt() {
 //   DMA  operands go global -> LDS directly (D a multiple of 64, H and W below 4 GiB each); otherwise
 //        through registers, with 64-bit addresses and a zero-filled last slab
 //   SEG  rows per segment of the packed token list: 32 (FWD_BLK) or 8 (FWD_SEG_SHORT)
+//   RES  resident workgroups: a workgroup walks several units (see the schedule below); without it the
+//        grid has one workgroup per unit and the code that moves on to a next unit is not generated
 // (Built and measured slower, and not kept as parameters: two 4-wave workgroups per CU on 256 x 128
 //  tiles, which move 1.5x the bytes into LDS, -20 %; 32-deep slabs in four stages, -6 %.)
 constexpr int FWD_NWN = 4;               // wave columns
-template <bool ARG, bool DMA, int SEG>
+template <bool ARG, bool DMA, int SEG, bool RES>
 __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdParams p) {
     static_assert(SEG == 32 || SEG == 16 || SEG == 8, "a segment is a whole number of a lane's register quads");
     constexpr int SPB = FWD_BLK / SEG;       // segments per row block
@@ -318,12 +320,18 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
     // ---- schedule.  A unit of work is (chunk, vocabulary tile); units are ordered in groups of gv
     //      vocabulary tiles x all chunks, so that units next to each other share rows of W and of H.
     //      Each XCD takes a contiguous range of the units (its L2 then sees gv tiles of W at a time), and
-    //      the workgroups of an XCD (one per CU, resident for the whole launch) deal that range out
-    //      round-robin: workgroup j walks units j, j + n, j + 2n, ... of the range.  Workgroup ids go
-    //      round-robin over the XCDs, so id & 7 is the XCD and id >> 3 the index on it. ----
+    //      the n workgroups of an XCD deal that range out round-robin: workgroup j walks units j, j + n,
+    //      j + 2n, ... of the range.  With RES the launch has one workgroup per CU, resident for the whole
+    //      launch; without it n is at least the length of the range, so every workgroup has at most one
+    //      unit and the hardware hands out units in order as CUs come free.  Workgroup ids go round-robin
+    //      over the XCDs, so id & 7 is the XCD and id >> 3 the index on it. ----
     const int n_segs = *p.n_blocks;
     const ChunkSplit cs = chunk_split(n_segs, p.tpc, SPT);
-    const int span = cs.nc * p.gv;                                       // units per group of vocabulary tiles
+    // units per group of vocabulary tiles.  One workgroup per unit: the unit list provides for the chunks
+    // of the longest possible token list, as the grid does, and the workgroups of chunks that do not exist
+    // return at once, in place (measured 1 % faster at B=64 S=512 than closing the gaps, which moves all
+    // idle workgroups to the end of the grid).
+    const int span = (RES ? cs.nc : p.n_chunks) * p.gv;
     const long long n_units = (long long)((p.n_vtiles + p.gv - 1) / p.gv) * span;
     const int n_local = gridDim.x >> 3;
     const int u_end = (int)(n_units * ((blockIdx.x & 7) + 1) / 8);
@@ -336,7 +344,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
             const int rem = u - vg * span;
             const int rc = rem / p.gv;
             const int vt = vg * p.gv + (rem - rc * p.gv);
-            if (vt >= p.n_vtiles) continue;
+            if (vt >= p.n_vtiles || rc >= cs.nc) continue;
             x.u = u; x.vt = vt; x.rc = rc;
             x.g0 = cs.first_tile(rc) * SPT;                                              // first segment of the chunk
             x.ns = min(n_segs, cs.first_tile(rc + 1) * SPT) - x.g0;                      // its segments
@@ -449,9 +457,10 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
         bool has_next = true;
         if (unit_ends) {
             nxt_t = 0;
-            has_next = open_unit(cur.u + n_local, nxt);
+            if constexpr (RES) has_next = open_unit(cur.u + n_local, nxt);
+            else has_next = false;
         }
-        if (t == 0 && tid < TN) {
+        if ((RES ? t == 0 : it == 0) && tid < TN) {
             // a unit begins: its output columns and bias; and whether its chunk begins inside a sequence
             // (until that sequence ends, the running pair is a later piece of it)
             v_out = cur.vt * TN + tid;
@@ -463,7 +472,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
         const bool pf_next = DMA && has_next && nk >= 2 && (nk & 1) == 0;
         if (!prefetched) {
             row_offsets(buf);
-            w_offsets(cur.vt);
+            if constexpr (RES) w_offsets(cur.vt);
         }
         // next tile's tables: in flight with the first slab, published by the slab loop's barriers
         if (has_next) fetch_rows(nxt, nxt_t, it + 1);
@@ -542,7 +551,7 @@ __global__ __launch_bounds__(fwd_threads(FWD_NWN), 2) void fwd_bf16_kernel(FwdPa
                 }
                 if (pf_next) {                                // nk is even: slab nk-1 lives in stage 1
                     row_offsets(buf ^ 1);                     // this tile's are no longer needed
-                    w_offsets(nxt.vt);
+                    if constexpr (RES) w_offsets(nxt.vt);
                     step(st1, steady, std::true_type{}, nk - 1);
                 }
                 if constexpr (NA > 0) {                       // last k-step of the last slab

@@ -47,26 +47,33 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 // Chunks of the packed forward (see fwd_bf16.hpp).  The host does not know the lengths, so it sizes the
 // grid and the workspace for the longest block list the shape allows (every sequence full:
 // B * ceil(S/32) blocks, 8 per tile); chunks beyond the real list return at once.
-// Tiles per chunk.  The (chunk, vocabulary tile) units are dealt round-robin to one resident workgroup
-// per CU, which walks its units back to back (the next unit's row table and first slab are prefetched
-// like the next tile's).  Long chunks mean fewer sequences cut at chunk boundaries (less to merge) and
-// fewer pieces to store; short chunks mean finer units, so that the last, partly filled round of units
-// costs little.  Four tiles where that leaves about 24 units per workgroup, else two, else one; depth is
-// estimated with sequences taken to fill 70 % of S.  Never more chunks than sequences: the per-chunk slots
-// for cut sequences (8 bytes per vocabulary entry) then stay below the size of the outputs Y and I,
-// whatever the sequence length.
+// Chunks and launch mode.  A unit of work is (chunk of tiles, vocabulary tile).
+// Deep problems launch one workgroup per unit, with chunks of four tiles: a workgroup that walks several
+// tiles hides the start of each behind the one before, the hardware hands the next unit to whichever CU
+// comes free (which keeps the CUs of an XCD on neighbouring units), and there are enough units that the
+// last, partly filled round costs little.  Chunk lengths 1 / 2 / 4 / 8 measured (forward ms): B=16 S=256
+// |V|=250002 0.966 / 0.944 / 0.958 / 1.007; B=64 S=512 D=1024 |V|=250002 8.91 / 8.92 / 8.78 / 8.95.
+// Shallow problems (fewer than 24 units of one tile per CU; depth is estimated with sequences taken to
+// fill 70 % of S) run one resident workgroup per CU over units of one tile each: no unit pays a workgroup
+// launch, the next unit's row table and first slab are prefetched like the next tile's, and the last round
+// is as full as the unit count allows (B=32 S=256 |V|=30522 and B=256 S=32: -1.5 to -3 %).  On deep problems
+// resident workgroups drift apart and lose L2 locality (B=64 S=512 |V|=250002: L2 hit rate 0.82 -> 0.76,
+// 16.1 -> 20.8 GB from the fabric, +1 % time), so they are not used there.
+// Never more chunks than sequences: the per-chunk slots for cut sequences (8 bytes per vocabulary entry)
+// then stay below the size of the outputs Y and I, whatever the sequence length.
 // Rows per segment of the packed token list: the MFMA row block, or 8 for batches of short sequences
 // (B=256, S=32, lengths 4..32: 8192 packed rows with 32-row segments, 5 400 with 8-row segments).
 int fwd_seg(const Shape& s) { return s.S <= FWD_SEG_SHORT_MAX_S ? FWD_SEG_SHORT : FWD_BLK; }
 
-struct FwdChunks { int tpc, n_chunks; bool cut_possible; };
+struct FwdChunks { int tpc, n_chunks; bool cut_possible, resident; };
 FwdChunks fwd_chunks(const Shape& s) {
     const int seg = fwd_seg(s);
     const long segs_max = (long)s.B * ((s.S + seg - 1) / seg);
     const long tiles_max = (segs_max * seg + FWD_TM - 1) / FWD_TM;
     FwdChunks c;
     const double units1 = 0.7 * (double)tiles_max * (double)((s.V + 255) / 256) / 256.0;      // per workgroup at one tile per chunk
-    c.tpc = units1 >= 96.0 ? 4 : (units1 >= 48.0 ? 2 : 1);
+    c.resident = units1 < 24.0;
+    c.tpc = c.resident ? 1 : 4;
     const long per_seq = (tiles_max + s.B - 1) / s.B;
     if (c.tpc < per_seq) c.tpc = (int)per_seq;
     c.n_chunks = (int)((tiles_max + c.tpc - 1) / c.tpc);
@@ -262,28 +269,33 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LSR_OK : L
 // Kernel choice: the direct-to-LDS ring when D is a multiple of the 64-wide K slab and H and W are
 // each below 4 GiB (32-bit byte offsets per lane), else the register-staged loader (64-bit addresses,
 // zero-fills the last slab).
-template <bool DMA, int SEG>
+template <bool DMA, int SEG, bool RES>
 void launch_fwd_cfg(FwdParams p, int V, bool arg, int n_cus, hipStream_t st) {
     constexpr int TN = fwd_tn(FWD_NWN);
     p.n_vtiles = (V + TN - 1) / TN;
     p.gv = FWD_GV_COLS / TN;
-    // one resident workgroup per CU (its LDS leaves room for no second one), a multiple of 8 so that every
-    // XCD gets the same number; each walks its share of the (chunk, vocabulary tile) units
-    const int n_wg = n_cus >= 8 ? n_cus / 8 * 8 : 8;
+    // RES: one resident workgroup per CU (its LDS leaves room for no second one), a multiple of 8 so that
+    // every XCD gets the same number.  Otherwise one workgroup per unit the longest possible token list
+    // would need (workgroups beyond the real list return at once).
+    const long long n_units = (long long)((p.n_vtiles + p.gv - 1) / p.gv) * p.gv * p.n_chunks;
+    const int n_wg = RES ? (n_cus >= 8 ? n_cus / 8 * 8 : 8) : (int)((n_units + 7) / 8 * 8);
     const dim3 grid(n_wg), block(fwd_threads(FWD_NWN));
-    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA, SEG>), grid, block, 0, st, p);
-    else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA, SEG>), grid, block, 0, st, p);
+    if (arg) hipLaunchKernelGGL((fwd_bf16_kernel<true, DMA, SEG, RES>), grid, block, 0, st, p);
+    else     hipLaunchKernelGGL((fwd_bf16_kernel<false, DMA, SEG, RES>), grid, block, 0, st, p);
 }
 
-void launch_fwd_bf16(const FwdParams& p, int seg, bool arg, int n_cus, hipStream_t st) {
+void launch_fwd_bf16(const FwdParams& p, int seg, bool resident, bool arg, int n_cus, hipStream_t st) {
     const bool small = (size_t)p.B * p.S * p.D * 2 < ((size_t)1 << 32) && (size_t)p.V * p.D * 2 < ((size_t)1 << 32);
     const bool dma = p.D % 64 == 0 && small;
-    if (seg == FWD_BLK) {
-        if (dma) launch_fwd_cfg<true, FWD_BLK>(p, p.V, arg, n_cus, st);
-        else launch_fwd_cfg<false, FWD_BLK>(p, p.V, arg, n_cus, st);
+    if (!dma) {          // the register-staged loader has no prefetch across units to gain from
+        if (seg == FWD_BLK) launch_fwd_cfg<false, FWD_BLK, false>(p, p.V, arg, n_cus, st);
+        else launch_fwd_cfg<false, FWD_SEG_SHORT, false>(p, p.V, arg, n_cus, st);
+    } else if (seg == FWD_BLK) {
+        if (resident) launch_fwd_cfg<true, FWD_BLK, true>(p, p.V, arg, n_cus, st);
+        else launch_fwd_cfg<true, FWD_BLK, false>(p, p.V, arg, n_cus, st);
     } else {
-        if (dma) launch_fwd_cfg<true, FWD_SEG_SHORT>(p, p.V, arg, n_cus, st);
-        else launch_fwd_cfg<false, FWD_SEG_SHORT>(p, p.V, arg, n_cus, st);
+        if (resident) launch_fwd_cfg<true, FWD_SEG_SHORT, true>(p, p.V, arg, n_cus, st);
+        else launch_fwd_cfg<true, FWD_SEG_SHORT, false>(p, p.V, arg, n_cus, st);
     }
 }
 
@@ -342,7 +354,7 @@ int forward_impl(const lsr_head_desc* desc, const void* H, const void* W, const 
         p.part_m = part_m; p.part_s = part_s;
         p.B = s.B; p.S = s.S; p.D = s.D; p.V = s.V;
         p.n_chunks = ck.n_chunks; p.tpc = ck.tpc;
-        launch_fwd_bf16(p, seg, I != nullptr, n_cus, st);
+        launch_fwd_bf16(p, seg, ck.resident, I != nullptr, n_cus, st);
     }
     prof.end(1);
     if (s.dtype == LSR_BF16 && ck.cut_possible) {
@@ -880,6 +892,7 @@ int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     plan[8] = dw_batch_chunk(s);
     plan[9] = fwd_chunks(s).n_chunks;
     plan[10] = fwd_seg(s);
+    plan[11] = fwd_chunks(s).resident ? 1 : 0;
     return LSR_OK;
 }
 

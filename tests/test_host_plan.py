@@ -20,14 +20,16 @@ def lib():
 
 def test_plans_of_the_benchmark_shapes():
     p = lsr.lsr_head_plan(64, 512, 1024, 250002, lsr.LSR_BF16)          # C5
-    assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "fwd_segment_rows": 32, "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
+    assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "fwd_segment_rows": 32, "fwd_resident_workgroups": 0,
+                 "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
                  "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64,
                  "dw_sequences_per_launch": 64}
     p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
     p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (1, 1, 16)
-    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"]) == (1, 32, 8)     # short sequences: 8-row segments
+    # short sequences: 8-row segments; a shallow grid: resident workgroups over one-tile units
+    assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"], p["fwd_resident_workgroups"]) == (1, 32, 8, 1)
     p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
     assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
     p = lsr.lsr_head_plan(256, 512, 768, 250002, lsr.LSR_BF16)          # a batch whose H slice is 4x L2: four dW launches
