@@ -44,9 +44,12 @@
 // leaves its pair in slot `chunk` of the part_m / part_s arrays; a small kernel (fwd_merge_kernel) joins
 // the pieces and finalises.  Chunks of whole sequences would need no such pass but end in short tiles
 // and need the lengths on the host to size.
-// One workgroup per CU stays resident for the whole launch and walks its share of the units (see the
-// schedule at the top of the kernel); the next unit's row table and first slab are prefetched like the
-// next tile's.
+// Two launch modes (template parameter RES, chosen by the host from the shape).  Deep problems launch
+// one workgroup per unit and let the hardware hand units out in order, which keeps the workgroups of an
+// XCD on neighbouring units and their shared rows of H and W in its L2.  Shallow problems (a few short
+// units per CU) launch one workgroup per CU that stays resident and walks its share of the units (see
+// the schedule at the top of the kernel), the next unit's row table and first slab prefetched like the
+// next tile's: there the launch and drain of a workgroup per unit would cost more than the drift.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
