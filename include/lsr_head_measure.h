@@ -78,8 +78,12 @@ int lsr_gather_probe(const void* table, size_t window_bytes, int steps, int laun
  *   [9] chunks the forward grid provides for (the longest token list the shape allows)
  *   [10] rows per segment of the packed token list (32, or 8 for batches of short sequences)
  *   [11] 1 if the forward runs one resident workgroup per CU over its units (shallow problems), else 0
+ *   [12] 1 if the column slices of the sliced dH gather are owned by XCDs (small batches), else 0
+ *   [13] copy passes per tile of the LDS-tile dW kernel (ceil(S / 128)), 0 when the gathers of [7] / [8] run
+ *        instead (the kernel applies to bfloat16 shapes with 128 <= S <= 512 and enough vocabulary rows to
+ *        give every CU a workgroup; it also needs dW to be requested)
  */
-#define LSR_PLAN_SLOTS 12
+#define LSR_PLAN_SLOTS 14
 int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan);
 
 #ifdef __cplusplus

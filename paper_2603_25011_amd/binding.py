@@ -171,7 +171,8 @@ def lsr_head_forward_profiled(B, S, D, V, hw_dtype, H, W, bias, mask, Y, I, work
 
 LSR_PLAN_FIELDS = ("fwd_tiles_per_chunk", "sort_segments", "sort_segment_len", "sort_places_through_lds",
                    "dh_chunks", "dh_chunk_len", "dh_buckets_per_wave", "dw_tile_rows", "dw_sequences_per_launch",
-                   "fwd_chunks", "fwd_segment_rows", "fwd_resident_workgroups")
+                   "fwd_chunks", "fwd_segment_rows", "fwd_resident_workgroups", "dh_slices_owned_by_xcd",
+                   "dw_lds_tile_passes")
 
 
 def lsr_head_plan(B, S, D, V, hw_dtype):

@@ -18,6 +18,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lds_dma.hpp"
+
 namespace lsr {
 
 constexpr int ROW_THREADS = 128;     // threads that share one row (16 bytes each per pass)
@@ -512,6 +514,48 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // ---------------------------------------------------------------------------------------------
 constexpr int DWS_COLS = 64;
 
+// Slices owned by XCDs.  Workgroup ids go round-robin over the chip's 8 XCDs (id & 7), each with an L2
+// of its own.  With n_dc = 8 q + r column slices, XCD x owns slices x, x + 8, ..., x + 8 (q - 1): every
+// gather from one of them goes through the same L2, which then holds one copy of the slice's window
+// instead of each of the eight L2s fetching its own, and sees all of the window's reuse.  The r slices
+// left over are shared: each is dealt out over all XCDs by item (item i goes to XCD i & 7).
+// An item is what the kernel iterates within a slice (a group of buckets).  A workgroup of the owned part
+// walks up to `walk` of its XCD's slices for one item; of the shared part, one slice.
+// Index j = id >> 3 of the workgroup on its XCD: first the owned part, ceil(q / walk) * n_items
+// workgroups, item fastest; then the shared part, r * ceil(n_items / 8).  The grid is 8 times the sum;
+// ids that fall behind the end of the shared part are not valid.
+struct XcdSliceUnit { bool valid, first_of_item; int item, dc_first, dc_step, dc_count; };
+__host__ __device__ inline long long xcd_slice_grid(int n_dc, int n_items, int walk) {
+    const int q = n_dc >> 3, r = n_dc & 7;
+    return 8ll * ((long long)((q + walk - 1) / walk) * n_items + (long long)r * ((n_items + 7) >> 3));
+}
+__host__ __device__ inline XcdSliceUnit xcd_slice_unit(unsigned id, int n_dc, int n_items, int walk) {
+    XcdSliceUnit u;
+    const int x = id & 7, j = (int)(id >> 3);
+    const int q = n_dc >> 3, r = n_dc & 7;
+    const int owned = ((q + walk - 1) / walk) * n_items;
+    if (j < owned) {
+        const int wg = j / n_items;                         // group of `walk` owned slices
+        u.item = j - wg * n_items;
+        u.dc_first = wg * walk * 8 + x;
+        u.dc_step = 8;
+        u.dc_count = (q < (wg + 1) * walk ? q : (wg + 1) * walk) - wg * walk;
+        u.first_of_item = x == 0 && wg == 0;
+        u.valid = true;
+    } else {
+        const int per = (n_items + 7) >> 3;
+        const int jj = j - owned;
+        const int l = jj / per;
+        u.item = (jj - l * per) * 8 + x;
+        u.dc_first = 8 * q + l;
+        u.dc_step = 1;
+        u.dc_count = 1;
+        u.first_of_item = q == 0 && l == 0;
+        u.valid = l < r && u.item < n_items;
+    }
+    return u;
+}
+
 template <typename T, bool COMPACT, typename OT>
 __global__ __launch_bounds__(256) void bwd_dw_sliced_kernel(const T* __restrict__ H,
                                                             const float* __restrict__ dY,
@@ -683,7 +727,7 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
                                                             const uint2* __restrict__ perm,
                                                             const float* prev_sum, OT* dH, int add_dst, int write_all,
                                                             int B, int S, int D, int V, int n_groups,
-                                                            int n_vc, int vc) {
+                                                            int n_vc, int vc, int xcd_own) {
     constexpr int N = RowChunk<T>::N;
     constexpr int LPR = DWS_COLS / N;          // lanes per row piece
     constexpr int G = 64 / BPW;                // lanes per bucket
@@ -693,12 +737,20 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
                                                // waves; C5 2.83 -> 3.71 ms)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int dc = blockIdx.x / n_groups;                          // slice-major order
+    int dc, g;
+    if (xcd_own) {                                                 // slices owned by XCDs (see xcd_slice_unit)
+        const XcdSliceUnit u = xcd_slice_unit(blockIdx.x, D / DWS_COLS, n_groups, 1);
+        if (!u.valid) return;
+        dc = u.dc_first;
+        g = u.item;
+    } else {
+        dc = blockIdx.x / n_groups;                                // slice-major order
+        g = blockIdx.x - dc * n_groups;
+    }
     // Within a slice, consecutive workgroups take the same positions of consecutive sequences
     // (b fastest).  Workgroups are dealt to the chip's shader engines in a fixed rotation; with s
     // fastest, the empty buckets behind the end of each sequence recur with a period that can leave
     // some engines with twice the work of others.
-    const int g = blockIdx.x - dc * n_groups;
     const int b = g % B;
     const int s = ((g / B) * 4 + wave) * BPW + lane / G;
     const bool live = s < S;
@@ -765,6 +817,145 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
         for (int i = 0; i < N / 4; ++i)
             OutVec<OT>::store4(dH + o + 4 * i, make_float4(prev[i].x + acc[4 * i], prev[i].y + acc[4 * i + 1],
                                                            prev[i].z + acc[4 * i + 2], prev[i].w + acc[4 * i + 3]));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dW/db, LDS-tile variant (bfloat16 inputs, D a multiple of 64, DWT_MIN_S <= S <= DWT_MAX_S).
+// A workgroup of 1024 threads owns 1024 consecutive vocabulary rows and one 64-column slice and walks
+// the sequences b = 0 .. B-1 in order.  For each sequence the slice of all S hidden states (S x 128
+// bytes, at most 64 KiB) is copied into LDS and every gather of the sequence is an LDS read.  Eight
+// lanes share a row piece (16 bytes each) and a thread keeps eight rows (64 float accumulators), so a
+// sequence costs one tile copy for 1024 gathers: the traffic out of L2 is the tile (S x 128 bytes)
+// instead of the gathers (1024 x 128 bytes), the reads are coalesced, and what is left is the arithmetic
+// of the gather itself, one unpack and one FMA per element, with the LDS reads running ahead of it.
+// The next sequence's tile travels global -> LDS directly (LDS-DMA, no staging registers) into the other
+// buffer while the current one is multiplied; its (dY, Y, I) travel through registers and are turned into
+// (g, tile row offset) pairs at the end of the round.  One barrier per sequence, behind a full vmcnt wait.
+// Pairs without gradient point at a row of zeros behind the tile (hidden states of padded positions are
+// never multiplied, whatever they hold), and a wave skips a pair of rows when none of its sixteen (row,
+// row group) entries has a gradient.  The order of the sums over b is the same as in the kernels above.
+// Not for sparse gradients (the cost does not fall with the number of non-zero pairs, as it does in the
+// compacting kernel above) or for few workgroups: the host takes it for shapes with at least one
+// workgroup per CU.
+// grid = ceil(V / 1024) * (D / 64), slice-major.  PASSES = ceil(S / 128) copy passes per tile.
+// ---------------------------------------------------------------------------------------------
+constexpr int DWT_ROWS = 1024;
+constexpr int DWT_MAX_S = 512;
+constexpr int DWT_MIN_S = 128;
+
+template <typename OT, int PASSES>
+__global__ __launch_bounds__(DWT_ROWS) void bwd_dw_tile_kernel(const uint16_t* __restrict__ H,
+                                                               const float* __restrict__ dY,
+                                                               const float* __restrict__ Y,
+                                                               const int* __restrict__ I,
+                                                               OT* dW, int add_dst, float* db, int add_db,
+                                                               int B, int S, int D, int V, int n_vtiles) {
+    constexpr int ROW_B = DWS_COLS * 2;                    // bytes per tile row
+    constexpr int RPT = 8;                                 // vocabulary rows per thread
+    constexpr int RGS = DWT_ROWS / 8;                      // row groups (eight lanes each) = tile rows per copy pass
+    static_assert(PASSES >= 1 && PASSES * RGS <= DWT_MAX_S, "tile rows");      // S <= PASSES * RGS
+    // two tiles, each followed by a row of zeros
+    __shared__ __attribute__((aligned(1024))) uint8_t s_tile[2][(DWT_MAX_S + 1) * ROW_B];
+    __shared__ float2 s_go[2][DWT_ROWS];                   // per pair: g, and (as int bits) the byte offset of its tile row
+    const int tid = threadIdx.x;
+    const int dc = blockIdx.x / n_vtiles;
+    const int v0 = (blockIdx.x - dc * n_vtiles) * DWT_ROWS;
+    const int rg = tid >> 3, cc = tid & 7;
+    const int vs = v0 + tid;                               // the row this thread stages
+    const bool vs_ok = vs < V;
+    const int vs_c = vs_ok ? vs : V - 1;
+
+    float acc[RPT][8];
+#pragma unroll
+    for (int k = 0; k < RPT; ++k)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[k][i] = 0.f;
+    float db_acc = (db && dc == 0 && add_db && vs_ok) ? db[vs] : 0.f;
+
+    // The loads of a sequence are straight-line code (clamped addresses instead of predicates) and nothing
+    // looks at their results before stage(), so that they stay in flight while the sequence before is
+    // multiplied.  Byte offsets within a sequence's hidden states (S * D * 2 bytes is far below 4 GiB) and
+    // within a row of dY / Y / I are kept in 32 bits; the sequence's base is wave-uniform.
+    float dy_r, y_r;
+    int ix_r;
+    uint32_t hoff[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) hoff[p] = (uint32_t)((min(p * RGS + rg, S - 1) * D + dc * DWS_COLS + cc * 8) * 2);
+    const uint32_t voff = (uint32_t)vs_c * 4u;
+    auto gload = [&](int b) {
+        const size_t ro = (size_t)b * V * 4;
+        dy_r = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dY) + ro + voff);
+        y_r = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(Y) + ro + voff);
+        ix_r = *reinterpret_cast<const int*>(reinterpret_cast<const char*>(I) + ro + voff);
+    };
+    // the eight tile rows a wave copies per pass land in 1024 contiguous LDS bytes, lane l at + 16 l; rows
+    // behind S - 1 (when S is not a multiple of 128) receive copies of row S - 1 and are never read
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((uint32_t)(tid >> 6) * 8u * ROW_B);
+    auto tile_load = [&](int b, int buf) {
+        const char* hb = reinterpret_cast<const char*>(H) + (size_t)b * S * D * 2;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr(&s_tile[buf][0])) + wave_lds;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) dma16_to_lds(hb, hoff[p], dst + p * RGS * ROW_B);
+    };
+    auto stage = [&](int buf, bool count) {
+        const float g = vs_ok ? gate_grad(dy_r, y_r) : 0.f;
+        db_acc += count ? g : 0.f;
+        s_go[buf][tid] = make_float2(g, __int_as_float((g != 0.f ? clamp_pos(ix_r, S) : DWT_MAX_S) * ROW_B));
+    };
+    if (tid < 16) *reinterpret_cast<uint4*>(&s_tile[tid >> 3][DWT_MAX_S * ROW_B + (tid & 7) * 16]) = make_uint4(0, 0, 0, 0);
+    gload(0);
+    tile_load(0, 0);
+    stage(0, true);
+    wait_vmcnt<0>();
+    __syncthreads();
+    for (int b = 0; b < B; ++b) {
+        const int buf = b & 1;
+        // the last round loads and stages the last sequence once more (into the buffer nobody reads again):
+        // no branch around the loads
+        const bool more = b + 1 < B;
+        gload(more ? b + 1 : b);
+        tile_load(more ? b + 1 : b, buf ^ 1);
+        // all eight (g, offset) pairs first, then the row pieces one pair of rows ahead of the FMAs that
+        // use them, so that a wave waits for LDS once per sequence rather than twice per pair of rows
+        float2 go[RPT];
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) go[k] = s_go[buf][rg + RGS * k];
+        const uint8_t* tile = &s_tile[buf][cc * 16];
+        uint4 xa = *reinterpret_cast<const uint4*>(tile + __float_as_int(go[0].y));
+        uint4 xb = *reinterpret_cast<const uint4*>(tile + __float_as_int(go[1].y));
+#pragma unroll
+        for (int h = 0; h < RPT; h += 2) {
+            uint4 na = xa, nb = xb;
+            if (h + 2 < RPT) {
+                na = *reinterpret_cast<const uint4*>(tile + __float_as_int(go[h + 2].y));
+                nb = *reinterpret_cast<const uint4*>(tile + __float_as_int(go[h + 3].y));
+            }
+            if (__any(go[h].x != 0.f || go[h + 1].x != 0.f)) {
+                RowChunk<uint16_t>::fma(xa, go[h].x, acc[h]);
+                RowChunk<uint16_t>::fma(xb, go[h + 1].x, acc[h + 1]);
+            }
+            xa = na;
+            xb = nb;
+        }
+        stage(buf ^ 1, more);
+        wait_vmcnt<0>();                               // the tile has landed
+        __syncthreads();
+    }
+    if (db && dc == 0 && vs_ok) db[vs] = db_acc;
+    if (!dW) return;
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        const int v = v0 + rg + RGS * k;
+        if (v < V) {
+            const size_t o = (size_t)v * D + dc * DWS_COLS + cc * 8;
+#pragma unroll
+            for (int i = 0; i < 8; i += 4) {
+                float4 r = make_float4(acc[k][i], acc[k][i + 1], acc[k][i + 2], acc[k][i + 3]);
+                if (add_dst) r = add4(OutVec<OT>::load4(dW + o + i), r);
+                OutVec<OT>::store4(dW + o + i, r);
+            }
+        }
     }
 }
 

@@ -397,9 +397,9 @@ void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const
 // One launch of the sliced dH gather (vocabulary chunk vc) / of the sliced dW gather (sequences b0 .. b0+nb-1).
 template <typename T, typename OT>
 void launch_dh_sliced(int bpw, dim3 grid, hipStream_t st, const T* W, const int* bounds, const uint2* perm, const float* prev,
-                      OT* dst, int add_dst, int write_all, const Shape& s, int n_groups, int n_vc, int vc) {
+                      OT* dst, int add_dst, int write_all, const Shape& s, int n_groups, int n_vc, int vc, bool xcd_own) {
 #define LSR_DH(BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW, OT>), grid, dim3(256), 0, st, W, bounds, perm, prev, dst, add_dst, \
-                                       write_all, s.B, s.S, s.D, s.V, n_groups, n_vc, vc)
+                                       write_all, s.B, s.S, s.D, s.V, n_groups, n_vc, vc, xcd_own ? 1 : 0)
     if (bpw == 1) LSR_DH(1);
     else if (bpw == 2) LSR_DH(2);
     else if (bpw == 4 || sizeof(T) == 4) LSR_DH(4);      // a float row piece takes 16 lanes: at most four buckets per wave
@@ -501,7 +501,28 @@ struct BwdLaunch {
     int dw_vt;               // rows of the dW staging tile: sliced gather if dw_sliced, else whole-row kernel
     bool dw_sliced;
     int dw_bc, dw_ndc, dw_slice_groups, dw_vtiles;
+    bool dh_xcd_own;         // sliced dH gather: column slices owned by XCDs
+    int dw_tile_passes;      // LDS-tile dW kernel: copy passes per tile (ceil(S / 128)), or 0 when it does not apply
+    int dw_tile_vtiles;
 };
+// The sliced dH gather with its column slices owned by XCDs (xcd_slice_unit).  In the slice-major order every
+// XCD fetches the slice's window of W for itself and sees one eighth of its reuse, which is B / 8 gathers
+// per row and vocabulary chunk; owned slices pay off while that is small.  Measured (dH, slice-major ->
+// owned): B=8 S=512 |V|=30522 0.062 -> 0.047 ms; B=16 S=256 |V|=250002 0.88 -> 0.73; B=32 S=256 |V|=250002
+// 1.06 -> 1.01; from B=32 at D=1024 on it loses (B=32 1.45 -> 1.67, B=64 S=512 2.65 -> 3.1: fewer L2 misses
+// but a slower kernel; the slice-major order happens to keep every sequence's bucket lists on one XCD).
+bool dh_slices_owned(const Shape& s) { return s.B <= 16; }
+// The LDS-tile dW kernel (bwd_dw_tile_kernel): bfloat16, D a multiple of 64, S within the tile, and at least
+// one workgroup per CU of a 256-CU device.  Measured against the sliced gather (dW): B=64 S=512 D=1024
+// |V|=250002 1.98 -> 1.72 ms; B=256 S=512 D=768 |V|=250002 7.84 -> 5.43; B=16 S=256 |V|=250002 0.407 ->
+// 0.363; B=256 S=512 |V|=30522 1.02 -> 0.94; B=8 S=512 |V|=30522 0.0445 -> 0.0463; 60 workgroups (D=128,
+// |V|=30522) 0.030 -> 0.052.
+int dw_tile_passes(const Shape& s) {
+    if (s.dtype != LSR_BF16 || s.D % DWS_COLS != 0 || s.S < DWT_MIN_S || s.S > DWT_MAX_S) return 0;
+    const long long units = (long long)((s.V + DWT_ROWS - 1) / DWT_ROWS) * (s.D / DWS_COLS);
+    if (units < 256 || units > 0x7fffffffll) return 0;
+    return (s.S + 127) / 128;
+}
 int plan_backward(const Shape& s, const BwdWs& w, BwdLaunch* L) {
     const int chunk_elems = s.dtype == LSR_F32 ? 4 : 8;
     const int n_chunks = s.D / chunk_elems;
@@ -512,6 +533,10 @@ int plan_backward(const Shape& s, const BwdWs& w, BwdLaunch* L) {
     L->bpw = L->dh_sliced ? dh_buckets_per_wave(s, w.n_vc) : 0;
     L->dh_groups = L->dh_sliced ? s.B * ((s.S + 4 * L->bpw - 1) / (4 * L->bpw)) : 0;
     if ((long long)L->dh_groups * (s.D / DWS_COLS) > 0x7fffffffll) return LSR_ERR_SHAPE;
+    L->dh_xcd_own = L->dh_sliced && dh_slices_owned(s);
+    if (L->dh_xcd_own && xcd_slice_grid(s.D / DWS_COLS, L->dh_groups, 1) > 0x7fffffffll) return LSR_ERR_SHAPE;
+    L->dw_tile_passes = dw_tile_passes(s);
+    L->dw_tile_vtiles = (s.V + DWT_ROWS - 1) / DWT_ROWS;
     // column-sliced dW gathers (L2-resident slices of H) need D % 64 == 0 and a (g, I) staging tile (at
     // most 48 KiB) at least 16 vocabulary rows wide, i.e. at most 384 sequences per launch.  Larger
     // batches keep the whole-row kernel, which also skips zero gradients.
@@ -635,7 +660,8 @@ int backward_launches(const Shape& s, const BwdWs& w, const BwdLaunch& L, const 
                                    s.B * s.S, s.S, s.V, w.n_vc, w.vc_len);
                 bounds = cb;
             }
-            const dim3 grid((unsigned)L.dh_groups * (unsigned)(s.D / DWS_COLS));
+            const dim3 grid(L.dh_xcd_own ? (unsigned)xcd_slice_grid(s.D / DWS_COLS, L.dh_groups, 1)
+                                         : (unsigned)L.dh_groups * (unsigned)(s.D / DWS_COLS));
             float* stage = reinterpret_cast<float*>(base + w.dh_stage_off);
             for (int vc = 0; vc < w.n_vc; ++vc) {
                 const bool last = vc + 1 == w.n_vc;
@@ -644,15 +670,15 @@ int backward_launches(const Shape& s, const BwdWs& w, const BwdLaunch& L, const 
                     float* d = reinterpret_cast<float*>(dH);
                     const bool fresh = vc == 0 && !accumulate;
                     launch_dh_sliced<T, float>(L.bpw, grid, st, W, bounds, perm, fresh ? nullptr : d, d, 0, fresh ? 1 : 0, s, L.dh_groups,
-                                               w.n_vc, vc);
+                                               w.n_vc, vc, L.dh_xcd_own);
                 } else if (w.n_vc == 1) {
                     launch_dh_sliced<T, OT>(L.bpw, grid, st, W, bounds, perm, nullptr, dH, accumulate, accumulate ? 0 : 1, s, L.dh_groups,
-                                            w.n_vc, vc);
+                                            w.n_vc, vc, L.dh_xcd_own);
                 } else if (!last) {
                     launch_dh_sliced<T, float>(L.bpw, grid, st, W, bounds, perm, vc > 0 ? stage : nullptr, stage, 0, vc == 0 ? 1 : 0, s,
-                                               L.dh_groups, w.n_vc, vc);
+                                               L.dh_groups, w.n_vc, vc, L.dh_xcd_own);
                 } else {
-                    launch_dh_sliced<T, OT>(L.bpw, grid, st, W, bounds, perm, stage, dH, accumulate, 1, s, L.dh_groups, w.n_vc, vc);
+                    launch_dh_sliced<T, OT>(L.bpw, grid, st, W, bounds, perm, stage, dH, accumulate, 1, s, L.dh_groups, w.n_vc, vc, L.dh_xcd_own);
                 }
             }
         } else {
@@ -664,7 +690,21 @@ int backward_launches(const Shape& s, const BwdWs& w, const BwdLaunch& L, const 
     if (dW || db) {
         prof.begin(4);
         const int VT = L.dw_vt;
-        if (L.dw_sliced) {
+        if (L.dw_tile_passes > 0 && dW) {
+            // one launch for all sequences; the sums start from zero, so bfloat16 results need no staging
+            if constexpr (sizeof(T) == 2) {
+                const dim3 grid((unsigned)L.dw_tile_vtiles * (unsigned)(s.D / DWS_COLS));
+#define LSR_DWT(NP) hipLaunchKernelGGL((bwd_dw_tile_kernel<OT, NP>), grid, dim3(DWT_ROWS), 0, st_dw, H, dY, Y, I, dW, accumulate, db, \
+                                       accumulate, s.B, s.S, s.D, s.V, L.dw_tile_vtiles)
+                switch (L.dw_tile_passes) {
+                    case 1: LSR_DWT(1); break;
+                    case 2: LSR_DWT(2); break;
+                    case 3: LSR_DWT(3); break;
+                    default: LSR_DWT(4); break;
+                }
+#undef LSR_DWT
+            }
+        } else if (L.dw_sliced) {
             // four waves also where the tile has fewer row groups than that (16 rows of bf16: two): the
             // others still share the staging and the compaction (C3: dW 0.264 -> 0.222 ms)
             const int waves = 4;
@@ -893,6 +933,8 @@ int lsr_head_plan(const lsr_head_desc* desc, int32_t* plan) {
     plan[9] = fwd_chunks(s).n_chunks;
     plan[10] = fwd_seg(s);
     plan[11] = fwd_chunks(s).resident ? 1 : 0;
+    plan[12] = (s.D % DWS_COLS == 0 && dh_slices_owned(s)) ? 1 : 0;
+    plan[13] = dw_tile_passes(s);
     return LSR_OK;
 }
 

@@ -62,6 +62,10 @@ def test_c1_tiny_fp32_forward_backward():
     (2, 1100, 64, 300, 900),    # just beyond: direct placement
     (3, 40, 64, 9000, 1),       # several sort segments per sequence, the last one short
     (260, 256, 64, 4100, 60),   # a batch whose H slice exceeds L2: the dW gather runs in three launches of 87 sequences
+    (2, 130, 128, 132000, 40),  # LDS-tile dW kernel: S just above one copy pass, ragged last vocabulary tile; dH slices dealt over XCDs
+    (3, 128, 576, 30000, 1),    # LDS-tile dW kernel, one pass; nine column slices: eight owned by XCDs, one shared
+    (2, 512, 64, 262200, 300),  # LDS-tile dW kernel at its longest sequence (four passes), one column slice
+    (17, 300, 128, 131100, 50), # LDS-tile dW kernel, three passes, S not a multiple of 128; slice-major dH
 ])
 def test_small_bf16_shapes(B, S, D, V, len_lo):
     inp = wl.make_custom(B, S, D, V, seed=B * 1000 + S, len_lo=len_lo)
@@ -256,6 +260,7 @@ def test_random_shapes_batched_long_and_wide():
     (260, 256, 64, 4100, 60),      # dW over three launches of sequences: staged likewise
     (3, 40, 200, 900, 1),          # D not a multiple of 64: whole-row kernels
     (450, 12, 64, 700, 1),         # whole-row dW beside sliced dH
+    (3, 200, 128, 131100, 20),     # LDS-tile dW kernel (dW requested) and the sliced gather (db alone)
 ])
 def test_bf16_gradient_outputs_and_accumulation(B, S, D, V, len_lo):
     """lsr_head_backward_ex: bfloat16 dH / dW (compared with the oracle within one bf16 step), and
@@ -312,6 +317,9 @@ def test_bf16_gradient_outputs_and_accumulation(B, S, D, V, len_lo):
     dW16b = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device=dev)
     run(lsr.LSR_BF16, False, None, dW16b, None)
     assert torch.equal(dW16b, f32[1].to(torch.bfloat16))
+    db_only = torch.full((V,), float("nan"), device=dev)
+    run(lsr.LSR_F32, False, None, None, db_only)
+    assert torch.equal(db_only, f32[2])
 
 
 def test_two_host_threads_on_two_streams():

@@ -23,15 +23,26 @@ def test_plans_of_the_benchmark_shapes():
     assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "fwd_segment_rows": 32, "fwd_resident_workgroups": 0,
                  "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
                  "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64,
-                 "dw_sequences_per_launch": 64}
+                 "dw_sequences_per_launch": 64, "dh_slices_owned_by_xcd": 0, "dw_lds_tile_passes": 4}
     p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
+    # a small batch: dH slices owned by XCDs; S = 256: the LDS-tile dW kernel with two copy passes per tile
+    assert (p["dh_slices_owned_by_xcd"], p["dw_lds_tile_passes"]) == (1, 2)
     p = lsr.lsr_head_plan(256, 32, 768, 30522, lsr.LSR_BF16)            # C3: one pass over a 30k vocabulary, 16-row dW tiles
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (1, 1, 16)
     # short sequences: 8-row segments; a shallow grid: resident workgroups over one-tile units
     assert (p["fwd_tiles_per_chunk"], p["fwd_chunks"], p["fwd_segment_rows"], p["fwd_resident_workgroups"]) == (1, 32, 8, 1)
+    assert (p["dh_slices_owned_by_xcd"], p["dw_lds_tile_passes"]) == (0, 0)      # S below the LDS-tile kernel's range
     p = lsr.lsr_head_plan(128, 8192, 768, 30522, lsr.LSR_BF16)          # long sequences: short buckets, direct placement
     assert (p["dh_buckets_per_wave"], p["sort_places_through_lds"], p["dh_chunks"]) == (8, 0, 1)
+    assert p["dw_lds_tile_passes"] == 0                                 # a sequence's slice does not fit an LDS tile
+    # the LDS-tile dW kernel needs a workgroup per CU: 1024 vocabulary rows x 64 columns each
+    assert lsr.lsr_head_plan(32, 256, 128, 30522, lsr.LSR_BF16)["dw_lds_tile_passes"] == 0      # 30 x 2 workgroups
+    assert lsr.lsr_head_plan(32, 256, 768, 30522, lsr.LSR_BF16)["dw_lds_tile_passes"] == 2      # 30 x 12
+    assert lsr.lsr_head_plan(32, 256, 768, 30522, lsr.LSR_F32)["dw_lds_tile_passes"] == 0       # bfloat16 only
+    assert lsr.lsr_head_plan(32, 513, 768, 30522, lsr.LSR_BF16)["dw_lds_tile_passes"] == 0
+    assert lsr.lsr_head_plan(32, 127, 768, 30522, lsr.LSR_BF16)["dw_lds_tile_passes"] == 0
+    assert lsr.lsr_head_plan(17, 128, 768, 30522, lsr.LSR_BF16)["dh_slices_owned_by_xcd"] == 0
     p = lsr.lsr_head_plan(256, 512, 768, 250002, lsr.LSR_BF16)          # a batch whose H slice is 4x L2: four dW launches
     assert (p["dw_sequences_per_launch"], p["dw_tile_rows"]) == (64, 64)
     p = lsr.lsr_head_plan(3, 40, 200, 900, lsr.LSR_BF16)                # D not a multiple of 64: whole-row kernels
