@@ -334,8 +334,13 @@ def main():
                     "gather_rate_cache_level_gbs": res["bwd_gather_bytes_cache_level"]
                     / ((res["kernel_ms"]["bwd_dH"] + res["kernel_ms"]["bwd_dW_db"]) * 1e-3) / 1e9,
                     "l2_counters": traffic.get("bwd_l2"),
+                    "sq_counters": traffic.get("bwd_sq"),
+                    # second bound of the gathers: one unpack and one FMA per gathered bf16 element, a wave-wide
+                    # instruction holding its SIMD for 4 cycles (no packed fp32): lane-ops / (CUs x 64 lanes per clock x clock)
+                    "gather_valu_floor_ms": 2.0 * res["nnz"] * w.D * 2.0 / (256 * 64 * 2.4e9) * 1e3,
                     "note": "achieved = compulsory bytes (every array once) / backward time; the gathers re-read rows of H and W "
-                            "from the caches (gather_bytes_cache_level), which is what bounds them"}
+                            "from the caches or LDS (gather_bytes_cache_level) and spend two VALU operations per gathered element "
+                            "(gather_valu_floor_ms: both gathers at full VALU issue rate, 2.4 GHz), which is what bounds them"}
         roof_bwd["frac"] = roof_bwd["achieved"] / roof_bwd["peak"]
         if traffic.get("bwd_bytes"):
             roof_bwd["traffic_rate_gbs"] = traffic["bwd_bytes"] / (res["bwd_ms"] * 1e-3) / 1e9

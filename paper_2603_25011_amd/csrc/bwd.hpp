@@ -513,6 +513,8 @@ __global__ __launch_bounds__(ROW_THREADS) void bwd_dw_kernel(const T* __restrict
 // dynamic LDS: B*VT floats + B*VT ints.   grid = ceil(V/VT) * ceil((D/64)/NDC).
 // ---------------------------------------------------------------------------------------------
 constexpr int DWS_COLS = 64;
+constexpr int DH_NLD = 4;                 // gathers in flight per lane of the sliced dH gather
+constexpr int PERM_SLACK = 256;           // entries the workspace keeps behind the sorted lists (see bwd_dh_sliced_kernel)
 
 // Slices owned by XCDs.  Workgroup ids go round-robin over the chip's 8 XCDs (id & 7), each with an L2
 // of its own.  With n_dc = 8 q + r column slices, XCD x owns slices x, x + 8, ..., x + 8 (q - 1): every
@@ -721,8 +723,8 @@ __global__ __launch_bounds__(256) void bwd_chunk_bounds_kernel(const int* __rest
     bounds[idx] = lo;
 }
 
-template <typename T, int BPW, typename OT>
-__global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict__ W,
+template <typename T, int BPW, typename OT, bool OFF32>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void bwd_dh_sliced_kernel(const T* __restrict__ W,
                                                             const int* __restrict__ bounds,
                                                             const uint2* __restrict__ perm,
                                                             const float* prev_sum, OT* dH, int add_dst, int write_all,
@@ -733,8 +735,9 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
     constexpr int G = 64 / BPW;                // lanes per bucket
     constexpr int EPG = G / LPR;               // entries of one bucket gathered per load
     static_assert(EPG >= 1, "a bucket needs at least one row piece worth of lanes");
-    constexpr int NLD = 4;                     // gathers in flight per lane (8: more registers, fewer
+    constexpr int NLD = DH_NLD;                // gathers in flight per lane (8: more registers, fewer
                                                // waves; C5 2.83 -> 3.71 ms)
+    static_assert(2 * G <= PERM_SLACK, "entries read behind the end of a list stay inside the slack");
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     int dc, g;
@@ -759,7 +762,6 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
     const int beg = live ? bounds[bi] : 0;
     const int end = live ? bounds[bi + 1] : 0;
     if (!write_all && !__any(beg < end)) return;      // nothing of this chunk in any bucket of the wave
-    const size_t prow = (size_t)b * V;
     const int col0 = dc * DWS_COLS + (lane % LPR) * N;
     const int sub = (lane % G) / LPR;
     const bool writer = live && sub == 0 && (write_all || beg < end);
@@ -780,33 +782,58 @@ __global__ __launch_bounds__(256) void bwd_dh_sliced_kernel(const T* __restrict_
             for (int i = 0; i < N / 4; ++i) prev[i] = add4(prev[i], OutVec<OT>::load4(dH + o + 4 * i));
         }
     }
-    // the (v, g) entries of the next NLD loads are fetched while the current rows are in flight, so
-    // the list read and the row gather it feeds never sit in one dependency chain
-    int nv[NLD];
-    float ng[NLD];
-    auto fetch_entries = [&](int base) {
+    // What limits this loop is the number of vector-memory instructions a CU can issue (counters: one every
+    // 20 cycles per CU with an entry load per gather, each holding the address path for about 16), so the
+    // (v, g) entries are not fetched per gather slot.  The G lanes of a bucket load G consecutive entries with
+    // one coalesced instruction, a block that feeds RPB rounds of NLD gathers per lane; a lane takes the
+    // entry of its slot from the lane that loaded it (ds_bpermute, which goes through the LDS crossbar, not
+    // the memory path).  The next block is in flight while the current one is used.  Rows are addressed as
+    // wave-uniform base + 32-bit byte offset where W allows it.  A slot behind the end of its list
+    // contributes through a zero gradient; the entry it reads belongs to a later bucket, to the next
+    // sequence, or to the PERM_SLACK entries the workspace keeps behind the last list (never written: the
+    // vocabulary index is clamped, the gradient not looked at).
+    constexpr int RPB = G / (NLD * EPG);       // rounds per block of entries
+    static_assert(RPB * NLD * EPG == G && RPB >= 1, "a block is a whole number of rounds");
+    const char* const Wb = reinterpret_cast<const char*>(W);
+    const uint2* const pl = perm + (size_t)b * V;                   // b: the same for the whole workgroup
+    const uint32_t row_bytes = (uint32_t)D * (uint32_t)sizeof(T);
+    const uint32_t col_bytes = (uint32_t)col0 * (uint32_t)sizeof(T);
+    const uint32_t vmax = (uint32_t)V - 1u;
+    const int li = lane % G;                   // lane within its bucket
+    const int src0 = (lane - li + sub) * 4;    // bpermute address of the lane holding entry `sub` of the block
+    uint2 cur = pl[beg + li];
+    for (int blk = beg; blk < end; blk += G) {
+        const uint2 nxt = pl[blk + G + li];
+        __builtin_amdgcn_sched_barrier(0);                          // the next block is requested first
 #pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            const int k = base + u * EPG + sub;
-            const bool ok = k < end;
-            const uint2 ent = ok ? perm[prow + k] : make_uint2(0u, 0u);
-            nv[u] = (int)ent.x;
-            ng[u] = __uint_as_float(ent.y);
+        for (int p = 0; p < RPB; ++p) {
+            const int rbase = blk + p * NLD * EPG;                  // first entry of the round
+            if (rbase < end) {                                      // the lanes of a bucket agree
+                // three phases, kept apart: the entries of all NLD slots, then all NLD gathers, then the FMAs
+                // (left to itself the compiler gathers two rows at a time)
+                uint32_t off[NLD];
+                float gq[NLD];
+                uint4 x[NLD];
+#pragma unroll
+                for (int u = 0; u < NLD; ++u) {
+                    const int from = src0 + (p * NLD * EPG + u * EPG) * 4;
+                    const uint32_t v = min((uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)cur.x), vmax);
+                    const int gy = __builtin_amdgcn_ds_bpermute(from, (int)cur.y);
+                    gq[u] = rbase + u * EPG + sub < end ? __int_as_float(gy) : 0.f;
+                    off[u] = OFF32 ? __umul24(v, row_bytes) + col_bytes : v;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < NLD; ++u) {
+                    if constexpr (OFF32) x[u] = *reinterpret_cast<const uint4*>(Wb + off[u]);
+                    else x[u] = *reinterpret_cast<const uint4*>(Wb + ((size_t)off[u] * row_bytes + col_bytes));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < NLD; ++u) RowChunk<T>::fma(x[u], gq[u], acc);
+            }
         }
-    };
-    fetch_entries(beg);
-    for (int base = beg; base < end; base += NLD * EPG) {
-        float g[NLD];
-        uint4 x[NLD];
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            g[u] = ng[u];
-            x[u] = make_uint4(0, 0, 0, 0);
-            if (g[u] != 0.f) x[u] = *reinterpret_cast<const uint4*>(W + (size_t)nv[u] * D + col0);
-        }
-        fetch_entries(base + NLD * EPG);
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) RowChunk<T>::fma(x[u], g[u], acc);
+        cur = nxt;
     }
 #pragma unroll
     for (int off = LPR; off < G; off <<= 1)

@@ -103,7 +103,7 @@ FwdWs fwd_ws(const Shape& s) {
     return w;
 }
 
-// ---- backward workspace: perm[B*V] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] |
+// ---- backward workspace: perm[B*V + PERM_SLACK] (v, g) pairs | cnt[B*n_seg*S] | bstart[B*(S+1)] |
 //      bounds[B*S*(n_vc+1)] (only when the dH gather is cut into n_vc > 1 vocabulary chunks) ----
 struct BwdWs { int n_seg, seg_len, key_bits, n_vc, vc_len; size_t perm_off, cnt_off, bs_off, cb_off, dh_stage_off, dw_stage_off, total; };
 
@@ -148,7 +148,7 @@ BwdWs bwd_ws(const Shape& s, bool bf16_out = false) {
     while ((1 << w.key_bits) < s.S) ++w.key_bits;
     const size_t bv = (size_t)s.B * s.V;
     w.perm_off = 0;
-    w.cnt_off = w.perm_off + align_up(sizeof(uint2) * bv);
+    w.cnt_off = w.perm_off + align_up(sizeof(uint2) * (bv + PERM_SLACK));
     w.bs_off = w.cnt_off + align_up(sizeof(int) * (size_t)s.B * w.n_seg * s.S);
     w.cb_off = w.bs_off + align_up(sizeof(int) * (size_t)s.B * (s.S + 1));
     dh_chunks(s, &w.n_vc, &w.vc_len);
@@ -398,13 +398,17 @@ void launch_dw(int cpt, dim3 grid, size_t lds, hipStream_t st, const T* H, const
 template <typename T, typename OT>
 void launch_dh_sliced(int bpw, dim3 grid, hipStream_t st, const T* W, const int* bounds, const uint2* perm, const float* prev,
                       OT* dst, int add_dst, int write_all, const Shape& s, int n_groups, int n_vc, int vc, bool xcd_own) {
-#define LSR_DH(BPW) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW, OT>), grid, dim3(256), 0, st, W, bounds, perm, prev, dst, add_dst, \
-                                       write_all, s.B, s.S, s.D, s.V, n_groups, n_vc, vc, xcd_own ? 1 : 0)
+    // 32-bit byte offsets into W (one multiply-add of 24-bit factors per gather) where W allows them
+    const bool off32 = (size_t)s.V * s.D * sizeof(T) <= 0xffffffffull && s.V <= (1 << 24) && (size_t)s.D * sizeof(T) < (1u << 24);
+#define LSR_DH2(BPW, O32) hipLaunchKernelGGL((bwd_dh_sliced_kernel<T, BPW, OT, O32>), grid, dim3(256), 0, st, W, bounds, perm, prev, dst, \
+                                             add_dst, write_all, s.B, s.S, s.D, s.V, n_groups, n_vc, vc, xcd_own ? 1 : 0)
+#define LSR_DH(BPW) do { if (off32) LSR_DH2(BPW, true); else LSR_DH2(BPW, false); } while (0)
     if (bpw == 1) LSR_DH(1);
     else if (bpw == 2) LSR_DH(2);
     else if (bpw == 4 || sizeof(T) == 4) LSR_DH(4);      // a float row piece takes 16 lanes: at most four buckets per wave
     else if constexpr (sizeof(T) == 2) LSR_DH(8);
 #undef LSR_DH
+#undef LSR_DH2
 }
 template <typename T, typename OT>
 void launch_dw_sliced(bool compact, dim3 grid, dim3 block, size_t lds, hipStream_t st, const T* H, const float* dY, const float* Y,

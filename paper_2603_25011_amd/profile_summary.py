@@ -74,7 +74,8 @@ FWD_KERNELS = ("lsr::fwd_prep_kernel", "lsr::fwd_plan_kernel", "lsr::fwd_rows_ke
                "lsr::fwd_bf16_kernel", "lsr::fwd_merge_kernel")
 BWD_KERNELS = ("lsr::bwd_count_kernel", "lsr::bwd_scan_kernel", "lsr::bwd_place_staged_kernel", "lsr::bwd_place_kernel",
                "lsr::bwd_chunk_bounds_kernel", "lsr::bwd_dh_sliced_kernel", "lsr::bwd_dw_sliced_kernel",
-               "lsr::bwd_dh_kernel", "lsr::bwd_dw_kernel")
+               "lsr::bwd_dw_tile_kernel", "lsr::bwd_dh_kernel", "lsr::bwd_dw_kernel")
+GATHER_KERNELS = ("lsr::bwd_dh_sliced_kernel", "lsr::bwd_dw_sliced_kernel", "lsr::bwd_dw_tile_kernel")
 
 
 def main():
@@ -155,7 +156,7 @@ def main():
             req, hit, miss = mean(c.get("TCC_REQ_sum", [])), mean(c.get("TCC_HIT_sum", [])), mean(c.get("TCC_MISS_sum", []))
             rate = hit / (hit + miss) if hit + miss > 0 else float("nan")
             lines.append("%-32s %10d %16.0f %16.0f %16.0f %9.3f" % (k, len(c.get("TCC_REQ_sum", [])), req, hit, miss, rate))
-            if k in ("lsr::bwd_dh_sliced_kernel", "lsr::bwd_dw_sliced_kernel"):
+            if k in GATHER_KERNELS:
                 l2_json[k] = {"req_per_dispatch": req, "hit_per_dispatch": hit, "miss_per_dispatch": miss, "hit_rate": rate}
         out["l2_counters"] = "\n".join(lines)
         traffic["bwd_l2"] = l2_json
@@ -178,6 +179,30 @@ def main():
             if c.get("SQ_INSTS_VALU_MFMA_MOPS_BF16"):
                 lines.append("flops issued = MOPS_BF16 x 512                 %.4g" % (c["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512.0))
         out["fwd_bf16_kernel_sq_counters"] = "\n".join(lines)
+
+    sqb = counters(os.path.join(d, "sqb"))
+    if any(sqb.get(k) for k in GATHER_KERNELS):
+        lines = ["rocprofv3 SQ counters of the backward's gather kernels, workload %s, MI355X, one GPU (mean per dispatch)." % args.workload,
+                 "  rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_LDS SQ_INSTS_VMEM_RD SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES SQ_BUSY_CYCLES \\",
+                 "      SQ_LDS_BANK_CONFLICT SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE -d gpurun_out/prof/sqb -o sqb --output-format csv -- \\",
+                 "      python3 bench.py --no-cpu --no-extra --steps 3 --warmup 1", "",
+                 "VALU issue share = SQ_INSTS_VALU x 4 cycles / (4 SIMDs x 256 CUs x cycles): a wave-wide fp32 or integer",
+                 "instruction occupies its SIMD's 16 lanes for 4 cycles (packed fp32 is not used)."]
+        sq_json = {}
+        for k in GATHER_KERNELS:
+            if not sqb.get(k):
+                continue
+            c = {n: mean(v) for n, v in sqb[k].items()}
+            lines += ["", k]
+            for n in sorted(c):
+                lines.append("  %-32s %18.4g" % (n, c[n]))
+            if c.get("GRBM_GUI_ACTIVE") and c.get("SQ_INSTS_VALU"):
+                cyc = c["GRBM_GUI_ACTIVE"] / 8.0
+                share = c["SQ_INSTS_VALU"] * 4.0 / (4.0 * 256.0 * cyc)
+                lines += ["  cycles per XCD (GRBM_GUI_ACTIVE / 8)  %.4g" % cyc, "  VALU issue share                      %.3f" % share]
+                sq_json[k] = {"valu_insts_per_dispatch": c["SQ_INSTS_VALU"], "cycles_per_dispatch": cyc, "valu_issue_share": share}
+        out["bwd_gather_sq_counters"] = "\n".join(lines)
+        traffic["bwd_sq"] = sq_json
 
     for tag, text in out.items():
         print("=" * 20, tag)

@@ -94,7 +94,8 @@ def test_plan_invariants_on_random_shapes():
             parts = 8 * p["fwd_chunks"] * V if (dt == lsr.LSR_BF16 and S > seg and p["fwd_chunks"] > 1) else 0
             assert tables + parts <= fw <= tables + parts + 8 * 256
             # the backward workspace holds what the plan implies
-            need = 8 * B * V + 4 * B * n_seg * S + 4 * B * (S + 1) + (4 * B * S * (c + 1) if c > 1 else 0)
+            # (the sorted (v, g) lists are followed by 256 entries of slack that the dH gather may read, never write)
+            need = 8 * (B * V + 256) + 4 * B * n_seg * S + 4 * B * (S + 1) + (4 * B * S * (c + 1) if c > 1 else 0)
             if S <= 8192 and B <= 6144:
                 ws = lsr.lsr_head_workspace_bytes(B, S, D, V, dt, True)
                 assert need <= ws <= need + 4 * 256
