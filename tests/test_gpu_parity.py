@@ -254,6 +254,32 @@ def test_random_shapes_batched_long_and_wide():
         run_case(inp, mask=mask)
 
 
+def test_random_shapes_lds_tile_dw():
+    """Seeded problems in the range of the LDS-tile dW kernel (128 <= S <= 512, at least 256 workgroups of 1024
+    vocabulary rows x 64 columns): few sequences against vocabularies wide enough for that, scattered masks
+    with empty sequences, gradients from dense to 2 % non-zero (pairs without gradient read the tile's row
+    of zeros; all-zero groups are skipped), D from one column slice to sixteen."""
+    from paper_2603_25011_amd import binding as b
+    rng = np.random.default_rng(20260327)
+    for case in range(8):
+        D = int(rng.choice([64, 128, 192, 256, 512, 1024]))
+        B = int(rng.integers(1, 5))
+        S = int(rng.integers(128, 513)) if case else 512
+        V = (256 * 1024 * 64) // D - int(rng.integers(0, 1024)) + (1024 if case % 2 else 3000)
+        V = max(V, (255 * 1024 * 64) // D + 1025)             # at least 256 vocabulary tiles x slices
+        plan = b.lsr_head_plan(B, S, D, V, b.LSR_BF16)
+        assert plan["dw_lds_tile_passes"] == (S + 127) // 128, plan
+        keep = float(rng.choice([0.3, 0.7, 1.0]))
+        density = float(rng.choice([0.02, 0.3, 1.0]))
+        inp = wl.make_custom(B, S, D, V, seed=9000 + case)
+        inp.dY[...] = inp.dY * (rng.random(inp.dY.shape) < density)
+        mask = wl.scattered_mask(rng, B, S, keep=keep)
+        if B > 2 and case % 3 == 0:
+            mask[int(rng.integers(0, B)), :] = 0
+        print(f"case {case}: B={B} S={S} D={D} V={V} keep={keep} gradient density={density}", flush=True)
+        run_case(inp, mask=mask)
+
+
 @pytest.mark.parametrize("B,S,D,V,len_lo", [
     (5, 70, 128, 640, 3),          # one launch each
     (2, 16, 128, 70000, 1),        # dH over three vocabulary chunks: float32 partial sums staged in the workspace
