@@ -139,6 +139,34 @@ def time_workload(name, steps, warmup, torch, wl, DeviceHead, rotate=False):
         res["fwd_ms_rotated_buffers"] = sum(e[0].elapsed_time(e[1]) for e in evr) / n_rot
         res["bwd_ms_rotated_buffers"] = sum(e[1].elapsed_time(e[2]) for e in evr) / n_rot
         del heads[1:]
+    if rotate:
+        # The same step recorded once into a HIP graph and replayed: what a serving or training loop that
+        # captures the head pays per step.  For the small configurations the gaps between the three to
+        # twelve launches of a step are a visible share of it; at C5 they are not.
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            n_rep = max(6, steps)
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(n_rep):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            res["ms_per_step_graph_replay"] = g0.elapsed_time(g1) / n_rep
+            del graph
+        except Exception as exc:          # a failed capture must not cost the headline line
+            res["ms_per_step_graph_replay"] = None
+            res["graph_replay_error"] = repr(exc)
     return res, inp, head
 
 
