@@ -523,6 +523,7 @@ bool dh_slices_owned(const Shape& s) { return s.B <= 16; }
 // |V|=30522) 0.030 -> 0.052.
 int dw_tile_passes(const Shape& s) {
     if (s.dtype != LSR_BF16 || s.D % DWS_COLS != 0 || s.S < DWT_MIN_S || s.S > DWT_MAX_S) return 0;
+    if (s.V > (1 << 28)) return 0;                       // the kernel keeps byte offsets within a row of dY / Y / I in 32 bits
     const long long units = (long long)((s.V + DWT_ROWS - 1) / DWT_ROWS) * (s.D / DWS_COLS);
     if (units < 256 || units > 0x7fffffffll) return 0;
     return (s.S + 127) / 128;
