@@ -789,22 +789,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     // entry of its slot from the lane that loaded it (ds_bpermute, which goes through the LDS crossbar, not
     // the memory path).  The next block is in flight while the current one is used.  Rows are addressed as
     // wave-uniform base + 32-bit byte offset where W allows it.  A slot behind the end of its list
-    // contributes through a zero gradient; the entry it reads belongs to a later bucket, to the next
-    // sequence, or to the PERM_SLACK entries the workspace keeps behind the last list (never written: the
-    // vocabulary index is clamped, the gradient not looked at).
+    // contributes through a zero gradient and gathers the row of the block's first entry instead (a row
+    // the bucket uses anyway, so nothing that could be non-finite is multiplied by that zero); the entry
+    // it read belongs to a later bucket, to the next sequence, or to the PERM_SLACK entries the workspace
+    // keeps behind the last list, and is not looked at.
     constexpr int RPB = G / (NLD * EPG);       // rounds per block of entries
     static_assert(RPB * NLD * EPG == G && RPB >= 1, "a block is a whole number of rounds");
     const char* const Wb = reinterpret_cast<const char*>(W);
     const uint2* const pl = perm + (size_t)b * V;                   // b: the same for the whole workgroup
     const uint32_t row_bytes = (uint32_t)D * (uint32_t)sizeof(T);
     const uint32_t col_bytes = (uint32_t)col0 * (uint32_t)sizeof(T);
-    const uint32_t vmax = (uint32_t)V - 1u;
     const int li = lane % G;                   // lane within its bucket
     const int src0 = (lane - li + sub) * 4;    // bpermute address of the lane holding entry `sub` of the block
     uint2 cur = pl[beg + li];
     for (int blk = beg; blk < end; blk += G) {
         const uint2 nxt = pl[blk + G + li];
         __builtin_amdgcn_sched_barrier(0);                          // the next block is requested first
+        const int v_first = __builtin_amdgcn_ds_bpermute((lane - li) * 4, (int)cur.x);      // entry blk: inside the list
 #pragma unroll
         for (int p = 0; p < RPB; ++p) {
             const int rbase = blk + p * NLD * EPG;                  // first entry of the round
@@ -817,9 +818,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 #pragma unroll
                 for (int u = 0; u < NLD; ++u) {
                     const int from = src0 + (p * NLD * EPG + u * EPG) * 4;
-                    const uint32_t v = min((uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)cur.x), vmax);
+                    const int vx = __builtin_amdgcn_ds_bpermute(from, (int)cur.x);
                     const int gy = __builtin_amdgcn_ds_bpermute(from, (int)cur.y);
-                    gq[u] = rbase + u * EPG + sub < end ? __int_as_float(gy) : 0.f;
+                    const bool inside = rbase + u * EPG + sub < end;
+                    const uint32_t v = (uint32_t)(inside ? vx : v_first);
+                    gq[u] = inside ? __int_as_float(gy) : 0.f;
                     off[u] = OFF32 ? __umul24(v, row_bytes) + col_bytes : v;
                 }
                 __builtin_amdgcn_sched_barrier(0);

@@ -254,6 +254,37 @@ def test_random_shapes_batched_long_and_wide():
         run_case(inp, mask=mask)
 
 
+@pytest.mark.parametrize("B,S,D,V", [
+    (5, 70, 128, 900),          # sliced gathers
+    (3, 200, 128, 131100),      # LDS-tile dW kernel: the tile copy brings masked rows into LDS
+    (4, 50, 72, 300),           # whole-row kernels, register-staged forward loader
+])
+def test_masked_positions_may_hold_anything(B, S, D, V):
+    """Hidden states at masked positions are never multiplied, in the forward or in the backward: with
+    NaN and infinities written there every output is bit-identical to the run on the clean input."""
+    inp = wl.make_custom(B, S, D, V, seed=77 + B, len_lo=3)
+    rng = np.random.default_rng(B)
+    mask = wl.scattered_mask(rng, B, S, keep=0.6)
+    clean = DeviceHead(inp, mask=mask)
+    clean.poison_outputs()
+    clean.forward()
+    clean.backward()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (clean.Y, clean.I, clean.dH, clean.dW, clean.db)]
+    dirty = DeviceHead(inp, mask=mask)
+    junk = torch.tensor([float("nan"), float("inf"), -float("inf")], device=dirty.dev)
+    pick = torch.randint(0, 3, (B, S, D), device=dirty.dev, generator=torch.Generator(device=dirty.dev).manual_seed(3))
+    masked = (dirty.mask == 0).view(B, S, 1).expand(B, S, D)
+    dirty.H = torch.where(masked, junk[pick].to(dirty.H.dtype), dirty.H).contiguous()
+    dirty.poison_outputs()
+    dirty.forward()
+    dirty.backward()
+    torch.cuda.synchronize()
+    for name, got, want in zip(("Y", "I", "dH", "dW", "db"), (dirty.Y, dirty.I, dirty.dH, dirty.dW, dirty.db), ref):
+        assert torch.equal(got, want), name
+    parity.compare_forward(inp, dirty.Y.cpu().numpy(), dirty.I.cpu().numpy(), mask=mask)
+
+
 def test_random_shapes_lds_tile_dw():
     """Seeded problems in the range of the LDS-tile dW kernel (128 <= S <= 512, at least 256 workgroups of 1024
     vocabulary rows x 64 columns): few sequences against vocabularies wide enough for that, scattered masks
