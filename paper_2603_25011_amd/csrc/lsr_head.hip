@@ -162,16 +162,15 @@ BwdWs bwd_ws(const Shape& s, bool bf16_out = false) {
 // Buckets a wave of the sliced dH gather serves.  The lanes of a bucket load its entries in blocks of as many
 // entries as the bucket has lanes (64 / k), two rounds of gathers per block.  Several buckets per wave pay
 // off when a bucket holds too few entries per chunk to keep a wave busy for several blocks, and cost when
-// their lists differ in length.  Measured optima (entries per bucket and chunk as estimated here -> k):
-// 1360 and 170 -> 1; 85 -> 2 in one pass over the vocabulary (B=256 S=512 |V|=30522: 0.92 / 0.77 / 0.80 /
-// 0.90 ms for k = 1 / 2 / 4 / 8), 2 or 4 alike in chunks (B=64 S=512 |V|=250002: 3.32 / 2.57 / 2.57 / 3.48)
-// or 4 (B=256 S=512 |V|=250002: 11.5 / 9.2 / 8.3 / 8.6); 5 -> 8 (B=128 S=8192: 4.4 / 2.4 / 1.55 / 1.37).
-// Lengths are not known on the host: sequences are taken to fill 70 % of S and every (b, v) pair to carry a
-// gradient.
+// their lists differ in length.  Lengths are not known on the host: sequences are taken to fill 70 % of S
+// and every (b, v) pair to carry a gradient.  Measured (dH ms for k = 1 / 2 / 4 / 8; entries per bucket and
+// chunk as estimated here, and as they really were): B=16 S=256 |V|=250002 (174; 217) 0.65 / 0.78 / 1.07 / -;
+// B=64 S=512 |V|=250002, lengths 128..512 (87; 98) 2.93 / 2.32 / 2.41 / 3.5; B=256 S=512 |V|=30522, full
+// lengths (85; 60) 0.91 / 0.75 / 0.79 / 0.90; B=256 S=512 |V|=250002, full lengths (87; 61) 9.3 / 8.0 / 7.7 /
+// 8.6; B=128 S=8192 |V|=30522 (5; 4) 4.4 / 2.4 / 1.55 / 1.37.
 int dh_buckets_per_wave(const Shape& s, int n_vc) {
     const double per_bucket = (double)s.V / ((0.7 * s.S > 1.0 ? 0.7 * s.S : 1.0) * n_vc);
-    const double two = n_vc > 1 ? 96.0 : 48.0;      // lists cut into vocabulary chunks: four buckets per wave up to 96 entries
-    int bpw = per_bucket >= 128.0 ? 1 : (per_bucket >= two ? 2 : (per_bucket >= 12.0 ? 4 : 8));
+    int bpw = per_bucket >= 128.0 ? 1 : (per_bucket >= 48.0 ? 2 : (per_bucket >= 12.0 ? 4 : 8));
     if (s.dtype == LSR_F32 && bpw > 4) bpw = 4;      // a float row piece takes 16 lanes
     return bpw;
 }

@@ -22,7 +22,7 @@ def test_plans_of_the_benchmark_shapes():
     p = lsr.lsr_head_plan(64, 512, 1024, 250002, lsr.LSR_BF16)          # C5
     assert p == {"fwd_tiles_per_chunk": 4, "fwd_chunks": 32, "fwd_segment_rows": 32, "fwd_resident_workgroups": 0,
                  "sort_segments": 64, "sort_segment_len": 3968, "sort_places_through_lds": 1,
-                 "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 4, "dw_tile_rows": 64,
+                 "dh_chunks": 8, "dh_chunk_len": 31251, "dh_buckets_per_wave": 2, "dw_tile_rows": 64,
                  "dw_sequences_per_launch": 64, "dh_slices_owned_by_xcd": 0, "dw_lds_tile_passes": 4}
     p = lsr.lsr_head_plan(16, 256, 768, 250002, lsr.LSR_BF16)           # C4: longer buckets, one per wave
     assert (p["dh_chunks"], p["dh_buckets_per_wave"], p["dw_tile_rows"]) == (8, 1, 64)
