@@ -801,15 +801,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     const uint32_t col_bytes = (uint32_t)col0 * (uint32_t)sizeof(T);
     const int li = lane % G;                   // lane within its bucket
     const int src0 = (lane - li + sub) * 4;    // bpermute address of the lane holding entry `sub` of the block
-    uint2 cur = pl[beg + li];
-    for (int blk = beg; blk < end; blk += G) {
-        const uint2 nxt = pl[blk + G + li];
+    const uint2* pe = pl + beg + li;           // this lane's entry of the current block
+    uint2 cur = *pe;
+    for (int left = end - beg; left > 0; left -= G) {               // entries from the block's start to the end of the list
+        pe += G;
+        const uint2 nxt = *pe;
         __builtin_amdgcn_sched_barrier(0);                          // the next block is requested first
-        const int v_first = __builtin_amdgcn_ds_bpermute((lane - li) * 4, (int)cur.x);      // entry blk: inside the list
+        const int v_first = __builtin_amdgcn_ds_bpermute((lane - li) * 4, (int)cur.x);      // the block's first entry: inside the list
+        const int rem = left - sub;                                 // slot at block offset c + sub is inside when c < rem
 #pragma unroll
         for (int p = 0; p < RPB; ++p) {
-            const int rbase = blk + p * NLD * EPG;                  // first entry of the round
-            if (rbase < end) {                                      // the lanes of a bucket agree
+            if (p * NLD * EPG < left) {                             // the round has entries; the lanes of a bucket agree
                 // three phases, kept apart: the entries of all NLD slots, then all NLD gathers, then the FMAs
                 // (left to itself the compiler gathers two rows at a time)
                 uint32_t off[NLD];
@@ -817,10 +819,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
                 uint4 x[NLD];
 #pragma unroll
                 for (int u = 0; u < NLD; ++u) {
-                    const int from = src0 + (p * NLD * EPG + u * EPG) * 4;
+                    const int c = p * NLD * EPG + u * EPG;          // block offset of the slot of sub-group 0
+                    const int from = src0 + c * 4;
                     const int vx = __builtin_amdgcn_ds_bpermute(from, (int)cur.x);
                     const int gy = __builtin_amdgcn_ds_bpermute(from, (int)cur.y);
-                    const bool inside = rbase + u * EPG + sub < end;
+                    const bool inside = c < rem;
                     const uint32_t v = (uint32_t)(inside ? vx : v_first);
                     gq[u] = inside ? __int_as_float(gy) : 0.f;
                     off[u] = OFF32 ? __umul24(v, row_bytes) + col_bytes : v;
